@@ -1,0 +1,112 @@
+/*
+ * convspmv.h -- C ABI of the padded-convolution-as-sparse-matrix library.
+ *
+ * A zero-padded, strided k x k convolution of an m x n input is one sparse
+ * matrix T of shape (m_out*n_out) x (m*n) applied to the row-major vectorised
+ * input (paper, Section 2: T = C P, result = vec^-1(T vec(A))).  T keeps only
+ * the kernel taps that fall on entries of A; their number is the closed form
+ * of Theorem 2.1.  The library builds T in CSR on the device and applies it
+ * to one vector (SpMV) or to a batch of vectors that share T (SpMM).
+ *
+ * Conventions
+ *   - Output pixel (x, y), 0 <= x < m_out, 0 <= y < n_out, is row x*n_out + y
+ *     of T; input pixel (i, j) is column i*n + j (row-major vec, Section 2).
+ *   - Tap (a, b) of window (x, y) touches input pixel (s*x + a - p,
+ *     s*y + b - p) and carries K[a*k + b]: no kernel flip (Section 2, first
+ *     row of C).  It is stored iff that pixel exists; it is stored even when
+ *     K[a*k + b] == 0, so nnz always equals the closed form.
+ *   - Entries of a row are in ascending column order (= (a, b) raster order).
+ *   - Indices are int32, values fp32.  All pointers named *_dev are device
+ *     (HIP) pointers owned by the caller; `stream` is a hipStream_t passed as
+ *     void* (NULL = the default stream).  Build and apply only enqueue work on
+ *     `stream`; they never synchronise it.
+ *   - Batches are batch-minor: element (pixel q, column c) at q*batch + c.
+ *
+ * Every function returns a status (0 = CONV_OK, negative = error) except
+ * conv_nnz, which returns the count or a negative status, and conv_strerror.
+ * No function throws or aborts.
+ */
+#ifndef CONVSPMV_H
+#define CONVSPMV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CONV_OK          0
+#define CONV_EINVAL     (-1)  /* m,n,k,s < 1, p < 0, batch < 1, or k > m+2p / n+2p (Theorem 2.1's precondition) */
+#define CONV_ENULL      (-2)  /* a required pointer is NULL */
+#define CONV_EOVERFLOW  (-3)  /* nnz, m*n, rows or an element count does not fit the 32-bit indices */
+#define CONV_EHIP       (-4)  /* a HIP call failed; see conv_last_hip_error */
+#define CONV_ENOMEM     (-5)  /* host or device allocation for the plan failed */
+#define CONV_EALIAS     (-6)  /* x and y overlap */
+
+typedef struct conv_plan conv_plan;   /* opaque host object */
+
+/* Theorem 2.1: m_out = floor((m+2p-k)/s)+1, n_out likewise.  Host only. */
+int conv_out_shape(int m, int n, int k, int s, int p, int *m_out, int *n_out);
+
+/* Theorem 2.1: number of stored entries of T,
+ *   sum_x sum_y max(0, k - c1(x)) * max(0, k - c2(y)),
+ * evaluated on the host in O(m_out + n_out) (the double sum of a product is
+ * the product of the two sums).  Returns the count (>= 0) or a status < 0.
+ * Counts above the int32 range are still returned exactly; conv_csr_build
+ * refuses them. */
+int64_t conv_nnz(int m, int n, int k, int s, int p);
+
+/* Build T in CSR on the device (Section 2 for what T holds, Theorem 2.1 for
+ * the row lengths: row (x, y) has max(0,k-c1(x)) * max(0,k-c2(y)) entries).
+ *   kernel_dev  : k*k fp32, row-major K[a*k + b], device, read by the build
+ *                 kernels on `stream` (must stay valid until they have run).
+ *   row_ptr_dev : (m_out*n_out + 1) int32, device, written.
+ *   col_idx_dev : nnz int32, device, written.   nnz = conv_nnz(m,n,k,s,p).
+ *   vals_dev    : nnz fp32,  device, written.
+ * The three CSR arrays are allocated by the caller and BORROWED by the plan:
+ * they must outlive it and must not be modified while an apply is in flight.
+ * The plan itself owns a small device table (the two per-axis prefix sums of
+ * the row-length factors, (m_out + n_out + 2) int32), allocated here with
+ * hipMalloc and released by conv_plan_destroy.
+ * On error nothing is enqueued and *plan_out is left NULL. */
+int conv_csr_build(int m, int n, int k, int s, int p,
+                   const float *kernel_dev,
+                   int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev,
+                   void *stream, conv_plan **plan_out);
+
+/* Apply: y = T x (Section 3, the convolution procedure: vec, multiply,
+ * un-vec; vec and its inverse are reinterpretations and move nothing).
+ *   x_dev : m*n*batch fp32, batch-minor, device, read.
+ *   y_dev : m_out*n_out*batch fp32, batch-minor, device, written (every
+ *           element; rows of T without entries give +0.0).
+ *   batch : number of vectors sharing T (1 = SpMV).
+ * The kernels read row_ptr, col_idx and vals as stored: the result is the
+ * product with whatever the three arrays hold, provided row_ptr is still
+ * non-decreasing with row lengths <= k*k and every col_idx is in [0, m*n).
+ * fp32 multiply-add, summation order unspecified but fixed (no atomics):
+ * repeated calls give bit-identical results.  x and y must not overlap. */
+int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch, void *stream);
+
+/* Shape and size queries on a plan (host only). */
+int conv_plan_shape(const conv_plan *plan, int *m, int *n, int *k, int *s, int *p,
+                    int *m_out, int *n_out, int64_t *nnz);
+
+/* Name of the apply variant conv_spmv would launch for this batch (static
+ * string, for reports), or NULL on bad arguments. */
+const char *conv_spmv_variant(const conv_plan *plan, int batch);
+
+/* Release the host object and the plan-owned device table.  The caller must
+ * have synchronised every stream the plan was used on.  NULL is accepted. */
+int conv_plan_destroy(conv_plan *plan);
+
+/* Static, human-readable text for a status code. */
+const char *conv_strerror(int status);
+
+/* hipError_t (as int) of the most recent failing HIP call made by this
+ * library on the calling thread; 0 if none. */
+int conv_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONVSPMV_H */

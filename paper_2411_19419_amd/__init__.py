@@ -1,0 +1,16 @@
+"""Padded, strided 2-D convolution as one CSR sparse matrix T, built and
+applied (SpMV / SpMM) by hand-written HIP kernels for gfx950.
+
+The compute lives in ``libconvspmv.so`` (C ABI declared in
+``include/convspmv.h``); ``binding`` marshals torch device pointers into it.
+"""
+from .binding import (  # noqa: F401
+    ConvError,
+    ConvPlan,
+    conv_csr_build,
+    conv_nnz,
+    conv_out_shape,
+    conv_spmv,
+    conv_strerror,
+    library_path,
+)

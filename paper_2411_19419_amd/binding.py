@@ -1,0 +1,183 @@
+"""Thin ctypes binding over libconvspmv.so: argument marshalling only.
+
+Names and meanings are those of ``include/convspmv.h``.  torch supplies device
+memory and the stream handle; every step of the path runs in the library's
+HIP kernels.  There is no fallback: if the shared library is missing or a call
+fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import threading
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIBNAME = "libconvspmv.so"
+_lock = threading.Lock()
+_lib = None
+
+EXPORTS = (
+    "conv_out_shape", "conv_nnz", "conv_csr_build", "conv_spmv", "conv_plan_shape",
+    "conv_spmv_variant", "conv_plan_destroy", "conv_strerror", "conv_last_hip_error",
+)
+
+
+class ConvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, conv_strerror(status), status))
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, _LIBNAME)
+
+
+def _load():
+    global _lib
+    with _lock:
+        if _lib is not None:
+            return _lib
+        path = library_path()
+        if not os.path.exists(path):
+            raise ImportError(
+                "%s is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                "from the repository root (hipcc --offload-arch=gfx950)" % path)
+        lib = ctypes.CDLL(path)
+        i, i64, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p
+        pi, pi64 = ctypes.POINTER(i), ctypes.POINTER(i64)
+        lib.conv_out_shape.argtypes = [i, i, i, i, i, pi, pi]
+        lib.conv_out_shape.restype = i
+        lib.conv_nnz.argtypes = [i, i, i, i, i]
+        lib.conv_nnz.restype = i64
+        lib.conv_csr_build.argtypes = [i, i, i, i, i, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]
+        lib.conv_csr_build.restype = i
+        lib.conv_spmv.argtypes = [vp, vp, vp, i, vp]
+        lib.conv_spmv.restype = i
+        lib.conv_plan_shape.argtypes = [vp, pi, pi, pi, pi, pi, pi, pi, pi64]
+        lib.conv_plan_shape.restype = i
+        lib.conv_spmv_variant.argtypes = [vp, i]
+        lib.conv_spmv_variant.restype = ctypes.c_char_p
+        lib.conv_plan_destroy.argtypes = [vp]
+        lib.conv_plan_destroy.restype = i
+        lib.conv_strerror.argtypes = [i]
+        lib.conv_strerror.restype = ctypes.c_char_p
+        lib.conv_last_hip_error.argtypes = []
+        lib.conv_last_hip_error.restype = i
+        _lib = lib
+        return lib
+
+
+def conv_strerror(status: int) -> str:
+    return _load().conv_strerror(int(status)).decode()
+
+
+def conv_out_shape(m, n, k, s, p):
+    mo, no = ctypes.c_int(), ctypes.c_int()
+    st = _load().conv_out_shape(m, n, k, s, p, ctypes.byref(mo), ctypes.byref(no))
+    if st != 0:
+        raise ConvError(st, "conv_out_shape%r" % ((m, n, k, s, p),))
+    return mo.value, no.value
+
+
+def conv_nnz(m, n, k, s, p) -> int:
+    v = int(_load().conv_nnz(m, n, k, s, p))
+    if v < 0:
+        raise ConvError(v, "conv_nnz%r" % ((m, n, k, s, p),))
+    return v
+
+
+def _stream_handle(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream), stream
+
+
+class ConvPlan:
+    """A built T: the three CSR tensors (torch, device) plus the library's
+    plan handle that borrows them."""
+
+    def __init__(self, handle, shape, out_shape, nnz, row_ptr, col_idx, vals, kernel):
+        self._handle = handle
+        self.m, self.n, self.k, self.s, self.p = shape
+        self.m_out, self.n_out = out_shape
+        self.nnz = nnz
+        self.row_ptr, self.col_idx, self.vals = row_ptr, col_idx, vals
+        self._kernel = kernel           # keep K alive until the build has run
+
+    @property
+    def rows(self):
+        return self.m_out * self.n_out
+
+    @property
+    def cols(self):
+        return self.m * self.n
+
+    def variant(self, batch: int) -> str:
+        v = _load().conv_spmv_variant(self._handle, int(batch))
+        return v.decode() if v else ""
+
+    def model_bytes(self, batch: int) -> int:
+        """Bytes a CSR SpMM has to move: entries (index + value), row_ptr,
+        x once, y once."""
+        return self.nnz * 8 + (self.rows + 1) * 4 + self.cols * batch * 4 + self.rows * batch * 4
+
+    def close(self):
+        if self._handle is not None:
+            import torch
+            torch.cuda.synchronize()
+            _load().conv_plan_destroy(self._handle)
+            self._handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def conv_csr_build(m, n, k, s, p, kernel, stream=None) -> ConvPlan:
+    """Build T on the device of `kernel` (a k*k float32 CUDA/HIP tensor)."""
+    import torch
+    lib = _load()
+    mo, no = conv_out_shape(m, n, k, s, p)
+    nnz = conv_nnz(m, n, k, s, p)
+    if not (kernel.is_cuda and kernel.dtype == torch.float32 and kernel.is_contiguous()
+            and kernel.numel() == k * k):
+        raise ValueError("kernel must be a contiguous float32 device tensor with k*k elements")
+    dev = kernel.device
+    if nnz >= 2 ** 31 or mo * no >= 2 ** 31 - 1:
+        raise ConvError(-3, "conv_csr_build%r" % ((m, n, k, s, p),))
+    row_ptr = torch.empty(mo * no + 1, dtype=torch.int32, device=dev)
+    col_idx = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)[:nnz]
+    vals = torch.empty(max(nnz, 1), dtype=torch.float32, device=dev)[:nnz]
+    handle = ctypes.c_void_p()
+    with torch.cuda.device(dev):
+        sh, _ = _stream_handle(stream)
+        st = lib.conv_csr_build(m, n, k, s, p, kernel.data_ptr(), row_ptr.data_ptr(),
+                                col_idx.data_ptr(), vals.data_ptr(), sh, ctypes.byref(handle))
+    if st != 0:
+        raise ConvError(st, "conv_csr_build%r" % ((m, n, k, s, p),))
+    return ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, row_ptr, col_idx, vals, kernel)
+
+
+def conv_spmv(plan: ConvPlan, x, y=None, batch: int = 1, stream=None):
+    """y = T x for `batch` batch-minor vectors.  Allocates y when not given."""
+    import torch
+    if plan._handle is None:
+        raise ValueError("plan is closed")
+    if not (x.is_cuda and x.dtype == torch.float32 and x.is_contiguous()):
+        raise ValueError("x must be a contiguous float32 device tensor")
+    if batch >= 1 and x.numel() != plan.cols * batch:
+        raise ValueError("x has %d elements, expected m*n*batch = %d" % (x.numel(), plan.cols * batch))
+    if y is None:
+        y = torch.empty(plan.rows * max(batch, 1), dtype=torch.float32, device=x.device)
+    elif not (y.is_cuda and y.dtype == torch.float32 and y.is_contiguous()
+              and y.numel() == plan.rows * batch):
+        raise ValueError("y must be a contiguous float32 device tensor with m_out*n_out*batch elements")
+    with torch.cuda.device(x.device):
+        sh, _ = _stream_handle(stream)
+        st = _load().conv_spmv(plan._handle, x.data_ptr(), y.data_ptr(), int(batch), sh)
+    if st != 0:
+        raise ConvError(st, "conv_spmv(batch=%d)" % batch)
+    return y
