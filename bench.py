@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the padded-convolution-as-SpMM path on one MI355X.
+
+Workload: the headline shape (m, n, k, s, p) = (1024, 1024, 7, 1, 3) with a
+batch of 16 vectors sharing T.  A step is one apply y = T x with T already
+built and x, T resident in HBM (the method builds T once and then applies it,
+paper Section 2); the build is timed in the same run and reported beside it.
+
+Prints ONE JSON line: effective HBM GB/s of the apply (model bytes = entries *
+(index + value) + row_ptr + x once + y once, divided by the time per step),
+useful MAC/s, build time, the roofline of the apply kernel (HIP events around
+single launches on the launch stream) and the CPU oracle timed on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+
+
+def cpu_baseline(w, x, K):
+    """The oracle as it stands, timed on the host cores on the whole workload
+    (one call as warm-up, then the median of repeated calls within ~20 s)."""
+    import numpy as np
+    import oracle
+    m, n, k, s, p = w.shape
+    oracle.conv(32, 32, 3, 1, 1, np.zeros(1024, np.float32), np.zeros(9, np.float32))   # load the library
+    times = []
+    t_all = time.perf_counter()
+    while len(times) < 5 and (time.perf_counter() - t_all < 20.0 or not times):
+        t0 = time.perf_counter()
+        oracle.conv(m, n, k, s, p, x, K, batch=w.batch)
+        times.append(time.perf_counter() - t0)
+    med = sorted(times)[len(times) // 2]
+    nnz = oracle.nnz_closed(m, n, k, s, p)
+    cores = int(os.environ.get("OMP_NUM_THREADS", "0")) or len(os.sched_getaffinity(0))
+    return {
+        "value": nnz * w.batch / med / 1e9, "unit": "GMAC/s (useful: closed-form nnz x batch / s)",
+        "seconds_per_apply": med, "cores": cores, "kind": "oracle",
+        "sample": "whole workload %s (%d calls, median); explicit zero-pad + sliding window, "
+                  "fp64 accumulation, OpenMP over output lines" % (w.name, len(times)),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default=None, help="name in workloads.WORKLOADS (default: the headline)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this path is built and timed on a single MI355X "
+                 "(--gpus %d is not supported)" % args.gpus)
+
+    import numpy as np
+    import torch
+
+    import __graft_entry__ as entry
+    if not os.path.exists(entry.LIB):
+        entry.build_library()
+    import paper_2411_19419_amd as cs
+    from paper_2411_19419_amd import workloads
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    dev = torch.device("cuda:0")
+    w = workloads.WORKLOADS[args.workload or workloads.HEADLINE]
+    m, n, k, s, p = w.shape
+    x_h, K_h = workloads.make(w)
+    x = torch.from_numpy(x_h).to(dev)
+    K = torch.from_numpy(K_h).to(dev)
+    stream = torch.cuda.current_stream()
+
+    # ---- build (row_ptr + fill kernels; allocation of the CSR arrays excluded from the event time)
+    plan = cs.conv_csr_build(m, n, k, s, p, K)
+    torch.cuda.synchronize()
+    build_ms = []
+    lib = cs.binding._load()
+    import ctypes
+    for _ in range(5):
+        h = ctypes.c_void_p()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        st = lib.conv_csr_build(m, n, k, s, p, K.data_ptr(), plan.row_ptr.data_ptr(), plan.col_idx.data_ptr(),
+                                plan.vals.data_ptr(), ctypes.c_void_p(stream.cuda_stream), ctypes.byref(h))
+        e1.record(stream)
+        torch.cuda.synchronize()
+        assert st == 0
+        lib.conv_plan_destroy(h)
+        build_ms.append(e0.elapsed_time(e1))
+    build_med = sorted(build_ms)[len(build_ms) // 2]
+
+    y = torch.empty(plan.rows * w.batch, dtype=torch.float32, device=dev)
+
+    # ---- warm-up, then exactly K steps between two synchronisations
+    for _ in range(args.warmup):
+        cs.conv_spmv(plan, x, y, batch=w.batch)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        cs.conv_spmv(plan, x, y, batch=w.batch)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    # ---- the apply kernel alone: HIP events around single launches on the launch stream
+    n_ev = min(args.steps, 100)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
+    for a, b in evs:
+        a.record(stream)
+        cs.conv_spmv(plan, x, y, batch=w.batch)
+        b.record(stream)
+    torch.cuda.synchronize()
+    kern_ms = sorted(a.elapsed_time(b) for a, b in evs)
+    kern_avg = sum(kern_ms) / len(kern_ms)
+
+    # ---- a plain copy of the same number of bytes, as the streaming ceiling of this machine
+    model_bytes = plan.model_bytes(w.batch)
+    src = torch.empty(model_bytes // 8, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record(stream)
+    for _ in range(20):
+        dst.copy_(src)
+    c1.record(stream)
+    torch.cuda.synchronize()
+    copy_gbs = 2 * src.numel() * 4 * 20 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del src, dst
+
+    gbs = model_bytes / (ms_per_step * 1e-3) / 1e9
+    achieved = model_bytes / (kern_avg * 1e-3) / 1e9
+    out = {
+        "metric": "SpMM effective HBM GB/s at 1024^2, k=7, batch 16 (model bytes / time per apply)"
+                  if w.name == workloads.HEADLINE else "SpMV/SpMM effective GB/s (model bytes / time per apply)",
+        "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "m": m, "n": n, "k": k, "s": s, "p": p, "batch": w.batch,
+                   "nnz": plan.nnz, "rows": plan.rows, "cols": plan.cols,
+                   "apply_variant": plan.variant(w.batch)},
+        "pct_of_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
+        "useful_mac_per_s": plan.nnz * w.batch / (ms_per_step * 1e-3),
+        "model_bytes": model_bytes,
+        "build_ms": build_med,
+        "build_over_apply": build_med / ms_per_step,
+        "copy_gbs_same_bytes": copy_gbs,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": plan.variant(w.batch), "kernel_ms_avg": kern_avg,
+                     "kernel_ms_median": kern_ms[len(kern_ms) // 2], "kernel_ms_min": kern_ms[0]},
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w, x_h, K_h)
+        out["gpu_over_cpu"] = out["useful_mac_per_s"] / 1e9 / out["cpu_baseline"]["value"]
+    plan.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,275 @@
+// Host side of the C ABI declared in include/convspmv.h: argument checking,
+// the closed-form count of Theorem 2.1, the plan object and kernel dispatch.
+#include "../../include/convspmv.h"
+
+#include <hip/hip_runtime.h>
+
+#include <new>
+
+#include "apply_kernels.h"
+#include "build_kernels.h"
+
+using namespace convspmv;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline bool hip_ok(hipError_t e) {
+    if (e == hipSuccess) return true;
+    g_last_hip_error = (int)e;
+    return false;
+}
+
+constexpr int64_t kInt32Limit = 2147483647LL;   // largest int32
+
+// Theorem 2.1, output extent along one axis (0 = precondition violated).
+int64_t out_extent(int64_t extent, int64_t k, int64_t s, int64_t p) {
+    if (k > extent + 2 * p) return 0;
+    return (extent + 2 * p - k) / s + 1;
+}
+
+int check_shape(int m, int n, int k, int s, int p, int64_t *mo, int64_t *no) {
+    if (m < 1 || n < 1 || k < 1 || s < 1 || p < 0) return CONV_EINVAL;
+    *mo = out_extent(m, k, s, p);
+    *no = out_extent(n, k, s, p);
+    if (*mo < 1 || *no < 1) return CONV_EINVAL;
+    return CONV_OK;
+}
+
+// Sum over one axis of max(0, k - c(t)), c(t) = max(0, p - s t) + max(0, s t + k - extent - p).
+int64_t axis_tap_sum(int64_t count, int64_t extent, int64_t k, int64_t s, int64_t p) {
+    int64_t total = 0;
+    for (int64_t t = 0; t < count; ++t) {
+        const int64_t lo = p - s * t, hi = s * t + k - extent - p;
+        const int64_t r = k - (lo > 0 ? lo : 0) - (hi > 0 ? hi : 0);
+        if (r > 0) total += r;
+    }
+    return total;
+}
+
+}  // namespace
+
+struct conv_plan {
+    ConvShape shape;
+    int64_t rows, cols, nnz;
+    int max_row_nnz;          // k*k
+    const int *row_ptr;       // borrowed, device
+    const int *col_idx;       // borrowed, device
+    const float *vals;        // borrowed, device
+    int *axis_tab;            // owned, device: P1[0..m_out], P2[0..n_out]
+    int device;
+};
+
+extern "C" {
+
+int conv_out_shape(int m, int n, int k, int s, int p, int *m_out, int *n_out) {
+    if (!m_out || !n_out) return CONV_ENULL;
+    int64_t mo, no;
+    const int st = check_shape(m, n, k, s, p, &mo, &no);
+    if (st != CONV_OK) return st;
+    if (mo > kInt32Limit || no > kInt32Limit) return CONV_EOVERFLOW;
+    *m_out = (int)mo;
+    *n_out = (int)no;
+    return CONV_OK;
+}
+
+int64_t conv_nnz(int m, int n, int k, int s, int p) {
+    int64_t mo, no;
+    const int st = check_shape(m, n, k, s, p, &mo, &no);
+    if (st != CONV_OK) return st;
+    const int64_t s1 = axis_tap_sum(mo, m, k, s, p);
+    const int64_t s2 = axis_tap_sum(no, n, k, s, p);
+    int64_t total;
+    if (__builtin_mul_overflow(s1, s2, &total)) return CONV_EOVERFLOW;
+    return total;
+}
+
+int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *row_ptr_dev,
+                   int32_t *col_idx_dev, float *vals_dev, void *stream, conv_plan **plan_out) {
+    if (!plan_out) return CONV_ENULL;
+    *plan_out = nullptr;
+    int64_t mo, no;
+    int st = check_shape(m, n, k, s, p, &mo, &no);
+    if (st != CONV_OK) return st;
+    const int64_t nnz = conv_nnz(m, n, k, s, p);
+    if (nnz < 0) return (int)nnz;
+    const int64_t rows = mo * no, cols = (int64_t)m * n;
+    // 32-bit indices: entries, columns, rows (+1 for row_ptr), the per-axis
+    // prefix sums, and the grids of the build kernels.
+    if (nnz > kInt32Limit || cols > kInt32Limit || rows >= kInt32Limit || (int64_t)k * k > kInt32Limit ||
+        mo * (int64_t)k > kInt32Limit || no * (int64_t)k > kInt32Limit)
+        return CONV_EOVERFLOW;
+    constexpr int G = 8;
+    const int64_t fill_blocks = mo * ((no + kFillThreads / G - 1) / (kFillThreads / G));
+    const int64_t rp_blocks = mo * ((no + kRowPtrThreads - 1) / kRowPtrThreads);
+    if (fill_blocks > kInt32Limit || rp_blocks > kInt32Limit) return CONV_EOVERFLOW;
+    if (!row_ptr_dev || !kernel_dev || (nnz > 0 && (!col_idx_dev || !vals_dev))) return CONV_ENULL;
+
+    conv_plan *plan = new (std::nothrow) conv_plan;
+    if (!plan) return CONV_ENOMEM;
+    plan->shape = ConvShape{m, n, k, s, p, (int)mo, (int)no};
+    plan->rows = rows;
+    plan->cols = cols;
+    plan->nnz = nnz;
+    plan->max_row_nnz = k * k;
+    plan->row_ptr = row_ptr_dev;
+    plan->col_idx = col_idx_dev;
+    plan->vals = vals_dev;
+    plan->axis_tab = nullptr;
+    plan->device = 0;
+    if (!hip_ok(hipGetDevice(&plan->device))) {
+        delete plan;
+        return CONV_EHIP;
+    }
+    if (!hip_ok(hipMalloc((void **)&plan->axis_tab, sizeof(int) * (size_t)(mo + no + 2)))) {
+        delete plan;
+        return CONV_ENOMEM;
+    }
+    hipStream_t q = (hipStream_t)stream;
+    axis_prefix_kernel<<<2, kAxisThreads, 0, q>>>(plan->shape, plan->axis_tab);
+    row_ptr_kernel<<<(unsigned)rp_blocks, kRowPtrThreads, 0, q>>>(plan->shape, plan->axis_tab, row_ptr_dev);
+    if (nnz > 0)
+        csr_fill_kernel<G><<<(unsigned)fill_blocks, kFillThreads, 0, q>>>(plan->shape, plan->axis_tab, kernel_dev,
+                                                                         col_idx_dev, vals_dev);
+    if (!hip_ok(hipGetLastError())) {
+        (void)hipFree(plan->axis_tab);
+        delete plan;
+        return CONV_EHIP;
+    }
+    *plan_out = plan;
+    return CONV_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+enum class Variant { GatherScalar, GatherVec4, GatherVec8, GatherVec16 };
+
+// Lanes per row for the row-group kernels: the narrowest power of two that
+// keeps the trip count at or below 8 (rows have at most k*k entries).
+int group_width(int max_row_nnz) {
+    int g = 1;
+    while (g < 16 && (max_row_nnz + g - 1) / g > 8) g <<= 1;
+    return g;
+}
+
+Variant pick_variant(const conv_plan *plan, const float *x, const float *y, int batch) {
+    (void)plan;
+    const bool aligned = ((((uintptr_t)x) | ((uintptr_t)y)) & 15u) == 0;
+    if (!aligned || batch % 4 != 0) return Variant::GatherScalar;
+    if (batch % 16 == 0) return Variant::GatherVec16;
+    if (batch % 8 == 0) return Variant::GatherVec8;
+    return Variant::GatherVec4;
+}
+
+const char *variant_name(Variant v) {
+    switch (v) {
+        case Variant::GatherScalar: return "rowgroup_gather_scalar";
+        case Variant::GatherVec4: return "rowgroup_gather_float4x1";
+        case Variant::GatherVec8: return "rowgroup_gather_float4x2";
+        case Variant::GatherVec16: return "rowgroup_gather_float4x4";
+    }
+    return "?";
+}
+
+template <int G>
+void launch_gather(Variant v, const conv_plan *plan, const float *x, float *y, int batch, hipStream_t q) {
+    const int rows = (int)plan->rows;
+    const unsigned bx = (unsigned)(((int64_t)rows * G + kGatherThreads - 1) / kGatherThreads);
+    auto by = [&](int per) { int b = batch / per; return (unsigned)(b > 65535 ? 65535 : b); };
+    switch (v) {
+        case Variant::GatherScalar:
+            spmm_gather_scalar_kernel<G><<<dim3(bx, by(1)), kGatherThreads, 0, q>>>(
+                plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch);
+            break;
+        case Variant::GatherVec4:
+            spmm_gather_vec_kernel<G, 1><<<dim3(bx, by(4)), kGatherThreads, 0, q>>>(
+                plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch);
+            break;
+        case Variant::GatherVec8:
+            spmm_gather_vec_kernel<G, 2><<<dim3(bx, by(8)), kGatherThreads, 0, q>>>(
+                plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch);
+            break;
+        case Variant::GatherVec16:
+            spmm_gather_vec_kernel<G, 4><<<dim3(bx, by(16)), kGatherThreads, 0, q>>>(
+                plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch);
+            break;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch, void *stream) {
+    if (!plan || !x_dev || !y_dev) return CONV_ENULL;
+    if (batch < 1) return CONV_EINVAL;
+    {   // x and y must not overlap
+        const char *xb = (const char *)x_dev, *xe = xb + sizeof(float) * (size_t)plan->cols * batch;
+        const char *yb = (const char *)y_dev, *ye = yb + sizeof(float) * (size_t)plan->rows * batch;
+        if (xb < ye && yb < xe) return CONV_EALIAS;
+    }
+    hipStream_t q = (hipStream_t)stream;
+    const Variant v = pick_variant(plan, x_dev, y_dev, batch);
+    switch (group_width(plan->max_row_nnz)) {
+        case 1: launch_gather<1>(v, plan, x_dev, y_dev, batch, q); break;
+        case 2: launch_gather<2>(v, plan, x_dev, y_dev, batch, q); break;
+        case 4: launch_gather<4>(v, plan, x_dev, y_dev, batch, q); break;
+        case 8: launch_gather<8>(v, plan, x_dev, y_dev, batch, q); break;
+        default: launch_gather<16>(v, plan, x_dev, y_dev, batch, q); break;
+    }
+    if (!hip_ok(hipGetLastError())) return CONV_EHIP;
+    return CONV_OK;
+}
+
+int conv_plan_shape(const conv_plan *plan, int *m, int *n, int *k, int *s, int *p, int *m_out, int *n_out,
+                    int64_t *nnz) {
+    if (!plan) return CONV_ENULL;
+    if (m) *m = plan->shape.m;
+    if (n) *n = plan->shape.n;
+    if (k) *k = plan->shape.k;
+    if (s) *s = plan->shape.s;
+    if (p) *p = plan->shape.p;
+    if (m_out) *m_out = plan->shape.m_out;
+    if (n_out) *n_out = plan->shape.n_out;
+    if (nnz) *nnz = plan->nnz;
+    return CONV_OK;
+}
+
+const char *conv_spmv_variant(const conv_plan *plan, int batch) {
+    if (!plan || batch < 1) return nullptr;
+    return variant_name(pick_variant(plan, nullptr, nullptr, batch));
+}
+
+int conv_plan_destroy(conv_plan *plan) {
+    if (!plan) return CONV_OK;
+    int st = CONV_OK;
+    if (plan->axis_tab) {
+        int cur = 0;
+        const bool have = hip_ok(hipGetDevice(&cur));
+        if (have && cur != plan->device) (void)hipSetDevice(plan->device);
+        if (!hip_ok(hipFree(plan->axis_tab))) st = CONV_EHIP;
+        if (have && cur != plan->device) (void)hipSetDevice(cur);
+    }
+    delete plan;
+    return st;
+}
+
+const char *conv_strerror(int status) {
+    switch (status) {
+        case CONV_OK: return "ok";
+        case CONV_EINVAL: return "invalid argument (need m,n,k,s >= 1, p >= 0, batch >= 1, k <= m+2p and k <= n+2p)";
+        case CONV_ENULL: return "required pointer is NULL";
+        case CONV_EOVERFLOW: return "size does not fit the library's 32-bit indices";
+        case CONV_EHIP: return "HIP call failed (see conv_last_hip_error)";
+        case CONV_ENOMEM: return "allocation failed";
+        case CONV_EALIAS: return "x and y overlap";
+    }
+    return "unknown status";
+}
+
+int conv_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,186 @@
+"""GPU parity: the HIP build and apply kernels, called through the C ABI,
+against the CPU oracle on the same seeded host arrays.  CSR arrays must be
+bit-exact; outputs within 1e-5 of the dot-product scale (see gpu_util)."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2411_19419_amd as cs
+from paper_2411_19419_amd import workloads
+
+from gpu_util import build_plan, check_apply, check_csr, device
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand(shape, batch, seed):
+    m, n, k, s, p = shape
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal(m * n * batch).astype(np.float32),
+            rng.standard_normal(k * k).astype(np.float32))
+
+
+def test_exhaustive_tiny_grid():
+    """Every valid shape with m, n <= 5, k <= 4, s <= 3, p <= 4 (k > m, p >= k
+    with empty rows, slide remainders), batch cycling through 1, 3, 4, 8."""
+    batches = itertools.cycle([1, 3, 4, 8])
+    count = 0
+    for shape in itertools.product(range(1, 6), range(1, 6), range(1, 5), range(1, 4), range(0, 5)):
+        m, n, k, s, p = shape
+        if k > m + 2 * p or k > n + 2 * p:
+            continue
+        batch = next(batches)
+        x, K = _rand(shape, batch, count)
+        plan = build_plan(shape, K)
+        check_csr(plan, shape, K)
+        check_apply(plan, shape, K, x, batch)
+        plan.close()
+        count += 1
+    assert count > 1000
+
+
+@pytest.mark.parametrize("shape", sorted(set(workloads.densenet121_layer_shapes())))
+@pytest.mark.parametrize("batch", [1, 8])
+def test_densenet_layer_shapes(shape, batch):
+    x, K = _rand(shape, batch, 100 + batch)
+    plan = build_plan(shape, K)
+    check_csr(plan, shape, K)
+    check_apply(plan, shape, K, x, batch)
+    plan.close()
+
+
+@pytest.mark.parametrize("name", list(workloads.WORKLOADS))
+def test_named_workloads_full_size(name):
+    """The measured configurations at their full sizes, every output compared."""
+    w = workloads.WORKLOADS[name]
+    x, K = workloads.make(w)
+    plan = build_plan(w.shape, K)
+    check_csr(plan, w.shape, K)
+    scaled, normwise = check_apply(plan, w.shape, K, x, w.batch)
+    print("%s: variant %s, max err/scale %.2e, normwise %.2e" % (name, plan.variant(w.batch), scaled, normwise))
+    plan.close()
+
+
+@pytest.mark.parametrize("shape,batch", [
+    ((37, 53, 7, 1, 3), 16),      # several tiles and a ragged tail in both directions
+    ((130, 67, 7, 1, 3), 16),
+    ((64, 64, 7, 1, 3), 16),
+    ((100, 90, 5, 2, 2), 16),
+    ((33, 200, 3, 1, 1), 32),
+    ((75, 75, 9, 3, 8), 4),
+    ((90, 41, 11, 4, 5), 4),
+    ((40, 40, 13, 1, 6), 2),      # k*k = 169 entries per row
+    ((30, 30, 17, 2, 8), 16),     # k*k = 289
+    ((50, 3, 3, 1, 1), 12),
+    ((3, 50, 7, 2, 3), 5),        # k > m
+    ((6, 6, 2, 1, 5), 7),         # p > k: mostly empty rows
+    ((1, 1, 1, 5, 2), 3),         # no entries at all
+    ((1, 1, 1, 1, 0), 1),
+    ((200, 1, 1, 1, 0), 6),
+])
+def test_ragged_and_degenerate_shapes(shape, batch):
+    x, K = _rand(shape, batch, 7)
+    plan = build_plan(shape, K)
+    check_csr(plan, shape, K)
+    check_apply(plan, shape, K, x, batch)
+    plan.close()
+
+
+@pytest.mark.parametrize("batch", [1, 2, 3, 4, 5, 8, 12, 16, 20, 24, 32, 48, 64])
+def test_batch_widths(batch):
+    shape = (45, 38, 5, 1, 2)
+    x, K = _rand(shape, batch, batch)
+    plan = build_plan(shape, K)
+    check_apply(plan, shape, K, x, batch)
+    plan.close()
+
+
+def test_unaligned_operands_take_the_scalar_path():
+    shape, batch = (29, 31, 3, 1, 1), 8
+    x, K = _rand(shape, batch, 3)
+    plan = build_plan(shape, K)
+    m, n, k, s, p = shape
+    buf = torch.zeros(x.size + 1, dtype=torch.float32, device=device())
+    buf[1:] = torch.from_numpy(x).to(device())
+    ybuf = torch.full((plan.rows * batch + 1,), float("nan"), dtype=torch.float32, device=device())
+    cs.conv_spmv(plan, buf[1:], ybuf[1:], batch=batch)
+    torch.cuda.synchronize()
+    ref, scale = oracle.conv(m, n, k, s, p, x, K, batch=batch, want_scale=True)
+    err = np.abs(ybuf[1:].cpu().numpy().astype(np.float64) - ref)
+    assert np.max(err / np.maximum(scale, 1e-30)) <= 1e-5
+    plan.close()
+
+
+def test_apply_reads_the_stored_arrays():
+    """Doubling vals doubles y; redirecting one stored column changes exactly
+    that row, by the amount a CSR product over the edited arrays gives."""
+    shape, batch = (40, 36, 5, 1, 2), 4
+    m, n, k, s, p = shape
+    x, K = _rand(shape, batch, 11)
+    plan = build_plan(shape, K)
+    xd = torch.from_numpy(x).to(device())
+    y0 = cs.conv_spmv(plan, xd, batch=batch).clone()
+    plan.vals.mul_(2.0)
+    y1 = cs.conv_spmv(plan, xd, batch=batch).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(y1, 2.0 * y0)
+    plan.vals.mul_(0.5)
+    rp, ci, va = oracle.csr(m, n, k, s, p, K)
+    row = 17 * plan.n_out + 9
+    e = int(rp[row]) + 3
+    new_col = (m - 1) * n + (n - 1)          # far away from the row's window
+    plan.col_idx[e] = new_col
+    y2 = cs.conv_spmv(plan, xd, batch=batch)
+    torch.cuda.synchronize()
+    y0h, y2h = y0.cpu().numpy().reshape(-1, batch), y2.cpu().numpy().reshape(-1, batch)
+    X = x.reshape(-1, batch).astype(np.float64)
+    changed = np.where(np.any(y0h != y2h, axis=1))[0]
+    assert changed.tolist() == [row]
+    ci2 = ci.copy()
+    ci2[e] = new_col
+    seg = slice(int(rp[row]), int(rp[row + 1]))
+    want = (va[seg].astype(np.float64)[:, None] * X[ci2[seg]]).sum(axis=0)
+    scale = (np.abs(va[seg]).astype(np.float64)[:, None] * np.abs(X[ci2[seg]])).sum(axis=0)
+    assert np.all(np.abs(y2h[row] - want) <= 1e-5 * scale)
+    plan.close()
+
+
+def test_repeatable_bit_for_bit_and_on_a_side_stream():
+    shape, batch = (96, 80, 7, 1, 3), 16
+    x, K = _rand(shape, batch, 5)
+    plan = build_plan(shape, K)
+    xd = torch.from_numpy(x).to(device())
+    y0 = cs.conv_spmv(plan, xd, batch=batch).clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        y1 = cs.conv_spmv(plan, xd, batch=batch)
+    side.synchronize()
+    y2 = cs.conv_spmv(plan, xd, batch=batch)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1) and torch.equal(y0, y2)
+    # a plan built on the side stream is identical too
+    with torch.cuda.stream(side):
+        plan2 = cs.conv_csr_build(*shape, torch.from_numpy(K).to(device()), stream=side)
+    side.synchronize()
+    assert torch.equal(plan.row_ptr, plan2.row_ptr) and torch.equal(plan.col_idx, plan2.col_idx)
+    assert torch.equal(plan.vals, plan2.vals)
+    plan.close()
+    plan2.close()
+
+
+def test_errors_on_device_calls():
+    shape = (8, 8, 3, 1, 1)
+    x, K = _rand(shape, 1, 1)
+    plan = build_plan(shape, K)
+    buf = torch.zeros(200, dtype=torch.float32, device=device())
+    with pytest.raises(cs.ConvError) as ei:
+        cs.conv_spmv(plan, buf[:64], buf[32:96], batch=1)        # overlapping x and y
+    assert ei.value.status == -6
+    with pytest.raises(cs.ConvError) as ei:
+        cs.conv_spmv(plan, buf[:64], buf[100:100], batch=0)
+    assert ei.value.status == -1
+    plan.close()

@@ -1,0 +1,123 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header
+declares, and its host-side logic (Theorem 2.1 count, output shape, argument
+validation) agrees with the oracle.  No kernel is launched here."""
+import ctypes
+import itertools
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2411_19419_amd as cs
+from paper_2411_19419_amd import binding, workloads
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "convspmv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(conv_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert set(names) == set(binding.EXPORTS)
+    lib = ctypes.CDLL(cs.library_path())
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_nnz_and_out_shape_match_oracle_on_tiny_grid():
+    count = 0
+    for m, n, k, s, p in itertools.product(range(1, 7), range(1, 7), range(1, 6), range(1, 4), range(0, 7)):
+        if k > m + 2 * p or k > n + 2 * p:
+            with pytest.raises(cs.ConvError) as ei:
+                cs.conv_nnz(m, n, k, s, p)
+            assert ei.value.status == -1
+            continue
+        assert cs.conv_nnz(m, n, k, s, p) == oracle.nnz_closed(m, n, k, s, p)
+        assert cs.conv_out_shape(m, n, k, s, p) == oracle.out_shape(m, n, k, s, p)
+        count += 1
+    assert count > 3000
+
+
+def test_nnz_on_named_workloads_and_layer_table():
+    want = {
+        "small_32_k3": 8836, "strided_256_k5_b64": 405769, "headline_1024_k7_b16": 51208336,
+        "cnn_224_k3_b256": 448900, "padheavy_512_k9_s3": 2359296, "padheavy_4096_k11_s4_b4": 126697536,
+    }
+    for name, nnz in want.items():
+        w = workloads.WORKLOADS[name]
+        assert cs.conv_nnz(*w.shape) == nnz
+    for shp in set(workloads.densenet121_layer_shapes()):
+        assert cs.conv_nnz(*shp) == oracle.nnz_brute(*shp)
+    # rectangular, k > m, p >= k
+    for shp in [(3, 50, 7, 2, 3), (2, 9, 5, 1, 2), (4, 4, 2, 3, 7), (1, 1, 1, 5, 2), (100, 3, 3, 1, 0)]:
+        assert cs.conv_nnz(*shp) == oracle.nnz_brute(*shp)
+
+
+def test_nnz_is_exact_beyond_int32():
+    # "same" 3x3 on 40000^2: (3*40000 - 2)^2 entries
+    assert cs.conv_nnz(40000, 40000, 3, 1, 1) == (3 * 40000 - 2) ** 2
+
+
+def test_argument_validation_without_a_gpu():
+    lib = binding._load()
+    for bad in [(0, 4, 1, 1, 0), (4, 0, 1, 1, 0), (4, 4, 0, 1, 0), (4, 4, 1, 0, 0), (4, 4, 1, 1, -1),
+                (4, 4, 7, 1, 1), (4, 9, 7, 1, 1)]:
+        assert lib.conv_nnz(*bad) == -1
+        mo, no = ctypes.c_int(), ctypes.c_int()
+        assert lib.conv_out_shape(*bad, ctypes.byref(mo), ctypes.byref(no)) == -1
+        h = ctypes.c_void_p()
+        assert lib.conv_csr_build(*bad, 16, 16, 16, 16, None, ctypes.byref(h)) == -1
+        assert h.value is None
+    assert lib.conv_out_shape(4, 4, 1, 1, 0, None, None) == -2
+    h = ctypes.c_void_p()
+    assert lib.conv_csr_build(4, 4, 3, 1, 1, None, None, None, None, None, ctypes.byref(h)) == -2
+    assert lib.conv_csr_build(4, 4, 3, 1, 1, 16, 16, 16, 16, None, None) == -2
+    # more entries than int32 indices can address
+    assert lib.conv_csr_build(40000, 40000, 3, 1, 1, 16, 16, 16, 16, None, ctypes.byref(h)) == -3
+    assert lib.conv_spmv(None, 16, 32, 1, None) == -2
+    assert lib.conv_plan_shape(None, *([None] * 8)) == -2
+    assert lib.conv_spmv_variant(None, 1) is None
+    assert lib.conv_plan_destroy(None) == 0
+
+
+def test_strerror_texts():
+    seen = set()
+    for code in range(0, -7, -1):
+        text = cs.conv_strerror(code)
+        assert text and text != "unknown status"
+        seen.add(text)
+    assert len(seen) == 7
+    assert cs.conv_strerror(-99) == "unknown status"
+
+
+def test_small_divisor_float_trick_is_exact():
+    """The device code divides small non-negative integers by multiplying
+    (a + 0.5) with a float reciprocal and truncating; check the claim over the
+    whole range it is used for, with the reciprocal off by one ulp either way."""
+    a = np.arange(0, 1 << 21, dtype=np.int64)
+    af = a.astype(np.float32) + np.float32(0.5)
+    for d in [1, 2, 3, 5, 7, 9, 11, 13, 25, 49, 121, 224, 1000, 1024, 4095, 4096, 4099, 65537]:
+        inv = np.float32(1.0) / np.float32(d)
+        for cand in (inv, np.nextafter(inv, np.float32(0)), np.nextafter(inv, np.float32(1))):
+            q = (af * cand).astype(np.int64)
+            assert np.array_equal(q, a // d), d
+
+
+def test_workload_generators_are_seeded_and_shaped():
+    w = workloads.WORKLOADS["small_32_k3"]
+    x1, k1 = workloads.make(w)
+    x2, k2 = workloads.make(w)
+    assert x1.dtype == np.float32 and k1.dtype == np.float32
+    assert x1.shape == (32 * 32,) and k1.shape == (9,)
+    assert np.array_equal(x1, x2) and np.array_equal(k1, k2)
+    assert np.all(np.abs(x1) <= 1.0)
+    w = workloads.WORKLOADS["headline_1024_k7_b16"]
+    k = workloads.make_kernel(w.k, w.k_std, w.seed)
+    assert abs(float(np.std(k)) - 1.0 / 7.0) < 0.05
+    assert len(workloads.densenet121_layer_shapes()) == 123
