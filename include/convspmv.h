@@ -91,8 +91,10 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
 int conv_plan_shape(const conv_plan *plan, int *m, int *n, int *k, int *s, int *p,
                     int *m_out, int *n_out, int64_t *nnz);
 
-/* Name of the apply variant conv_spmv would launch for this batch (static
- * string, for reports), or NULL on bad arguments. */
+/* Name of the apply variant conv_spmv would launch for this batch with
+ * 16-byte-aligned x and y (for reports), or NULL on bad arguments.  The text
+ * lives in a per-thread buffer and is valid until the next call on that
+ * thread. */
 const char *conv_spmv_variant(const conv_plan *plan, int batch);
 
 /* Release the host object and the plan-owned device table.  The caller must

@@ -54,10 +54,9 @@ __global__ __launch_bounds__(kGatherThreads) void spmm_gather_vec_kernel(
         end = row_ptr[row + 1];
     }
     for (int c0 = blockIdx.y * (4 * NV); c0 < batch; c0 += gridDim.y * (4 * NV)) {   // uniform over the block
-    float4 acc[NV];
+        float4 acc[NV];
 #pragma unroll
-    for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
-    {
+        for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int e = beg + lane; e < end; e += G) {
             const float w = vals[e];
             const float4 *xr = reinterpret_cast<const float4 *>(x + (long long)col_idx[e] * batch + c0);
@@ -70,19 +69,18 @@ __global__ __launch_bounds__(kGatherThreads) void spmm_gather_vec_kernel(
                 acc[v].w = fmaf(w, xv.w, acc[v].w);
             }
         }
-    }
 #pragma unroll
-    for (int v = 0; v < NV; ++v) {
-        acc[v].x = group_sum<G>(acc[v].x);
-        acc[v].y = group_sum<G>(acc[v].y);
-        acc[v].z = group_sum<G>(acc[v].z);
-        acc[v].w = group_sum<G>(acc[v].w);
-    }
-    if (row < rows && lane == 0) {
-        float4 *yr = reinterpret_cast<float4 *>(y + row * batch + c0);
+        for (int v = 0; v < NV; ++v) {
+            acc[v].x = group_sum<G>(acc[v].x);
+            acc[v].y = group_sum<G>(acc[v].y);
+            acc[v].z = group_sum<G>(acc[v].z);
+            acc[v].w = group_sum<G>(acc[v].w);
+        }
+        if (row < rows && lane == 0) {
+            float4 *yr = reinterpret_cast<float4 *>(y + row * batch + c0);
 #pragma unroll
-        for (int v = 0; v < NV; ++v) yr[v] = acc[v];
-    }
+            for (int v = 0; v < NV; ++v) yr[v] = acc[v];
+        }
     }
 }
 

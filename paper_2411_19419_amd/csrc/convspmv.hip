@@ -4,9 +4,11 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
 #include <new>
 
 #include "apply_kernels.h"
+#include "apply_tile_kernel.h"
 #include "build_kernels.h"
 
 using namespace convspmv;
@@ -145,57 +147,163 @@ int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, i
 
 namespace {
 
-enum class Variant { GatherScalar, GatherVec4, GatherVec8, GatherVec16 };
+// ---------------------------------------------------------------------------
+// Apply dispatch
+// ---------------------------------------------------------------------------
+enum class Kind { GatherScalar, GatherVec, Tile };
 
-// Lanes per row for the row-group kernels: the narrowest power of two that
-// keeps the trip count at or below 8 (rows have at most k*k entries).
+struct ApplyChoice {
+    Kind kind;
+    int g;          // lanes per row
+    int nit;        // entries per lane (tile kernel: compile-time trip count)
+    int nv;         // float4 column chunks per lane (0 = scalar columns)
+    int threads;
+    size_t lds;
+    TileGeom geom;
+};
+
+// Lanes per row for the gather kernels: the narrowest power of two that keeps
+// the trip count at or below 8 (rows have at most k*k entries).
 int group_width(int max_row_nnz) {
     int g = 1;
     while (g < 16 && (max_row_nnz + g - 1) / g > 8) g <<= 1;
     return g;
 }
 
-Variant pick_variant(const conv_plan *plan, const float *x, const float *y, int batch) {
-    (void)plan;
-    const bool aligned = ((((uintptr_t)x) | ((uintptr_t)y)) & 15u) == 0;
-    if (!aligned || batch % 4 != 0) return Variant::GatherScalar;
-    if (batch % 16 == 0) return Variant::GatherVec16;
-    if (batch % 8 == 0) return Variant::GatherVec8;
-    return Variant::GatherVec4;
+constexpr size_t kLdsPerCu = 160 * 1024;
+constexpr int kTileG = 8;
+const int kTileNit[] = {2, 4, 7, 11, 16};
+
+// Tile shapes tried in order: {output lines, output pixels per line, threads}.
+const int kTileShapes[][3] = {{8, 64, 512}, {8, 32, 256}, {4, 32, 128}, {2, 32, 64}};
+
+int round_up_mod(int v, int mod, int rem) {      // smallest r >= v with r % mod == rem
+    int r = v - (v % mod) + rem;
+    return r < v ? r + mod : r;
 }
 
-const char *variant_name(Variant v) {
-    switch (v) {
-        case Variant::GatherScalar: return "rowgroup_gather_scalar";
-        case Variant::GatherVec4: return "rowgroup_gather_float4x1";
-        case Variant::GatherVec8: return "rowgroup_gather_float4x2";
-        case Variant::GatherVec16: return "rowgroup_gather_float4x4";
+bool tile_geometry(const conv_plan *plan, int batch, int nv, int th, int tw, TileGeom *out, size_t *lds) {
+    const ConvShape &sh = plan->shape;
+    TileGeom g{};
+    g.m = sh.m; g.n = sh.n; g.m_out = sh.m_out; g.n_out = sh.n_out; g.s = sh.s; g.p = sh.p;
+    g.batch = batch;
+    g.th = th; g.tw = tw;
+    g.tiles_x = (sh.n_out + tw - 1) / tw;
+    g.tiles_y = (sh.m_out + th - 1) / th;
+    const int64_t n_tiles = (int64_t)g.tiles_x * g.tiles_y;
+    const int64_t ih = (int64_t)(th - 1) * sh.s + sh.k, iw = (int64_t)(tw - 1) * sh.s + sh.k;
+    // int arithmetic in the kernel: s*x0 - p, i_lo + ih, ihc * n (float-reciprocal division needs < 2^21)
+    if ((int64_t)sh.m + 2LL * sh.p + ih >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + iw >= (1LL << 30)) return false;
+    if (ih * sh.n >= (1LL << 21) || n_tiles + kXcds >= (1LL << 31) / kXcds) return false;
+    g.n_tiles = (int)n_tiles;
+    g.tiles_per_xcd = (int)((n_tiles + kXcds - 1) / kXcds);
+    g.ih = (int)ih; g.iw = (int)iw;
+    g.iw_pitch = round_up_mod((int)iw, 16, 8);
+    const int64_t plane = ih * g.iw_pitch;
+    if (plane * nv >= (1LL << 21)) return false;
+    g.chunk_stride = round_up_mod((int)plane, 16, 4);
+    g.inv_n = 1.0f / (float)sh.n;
+    *lds = (size_t)nv * g.chunk_stride * 16 + (size_t)th * (tw + 1) * 4;
+    *out = g;
+    return true;
+}
+
+ApplyChoice choose_apply(const conv_plan *plan, const float *x, const float *y, int batch) {
+    ApplyChoice c{};
+    const bool aligned = ((((uintptr_t)x) | ((uintptr_t)y)) & 15u) == 0;
+    c.g = group_width(plan->max_row_nnz);
+    if (!aligned || batch % 4 != 0) {
+        c.kind = Kind::GatherScalar;
+        c.nv = 0;
+        c.threads = kGatherThreads;
+        return c;
     }
-    return "?";
+    c.nv = batch % 16 == 0 ? 4 : (batch % 8 == 0 ? 2 : 1);
+    c.kind = Kind::GatherVec;
+    c.threads = kGatherThreads;
+    // LDS-tiled kernel when the rows fit its unrolled trip count and a tile
+    // leaves room for two workgroups per CU
+    const int need = (plan->max_row_nnz + kTileG - 1) / kTileG;
+    int nit = 0;
+    for (int cand : kTileNit)
+        if (cand >= need) { nit = cand; break; }
+    if (nit == 0 || batch / (4 * c.nv) > 65535) return c;
+    for (const auto &shp : kTileShapes) {
+        TileGeom g;
+        size_t lds;
+        if (!tile_geometry(plan, batch, c.nv, shp[0], shp[1], &g, &lds)) continue;
+        if (lds > kLdsPerCu / 2) continue;
+        c.kind = Kind::Tile;
+        c.g = kTileG;
+        c.nit = nit;
+        c.threads = shp[2];
+        c.lds = lds;
+        c.geom = g;
+        break;
+    }
+    return c;
 }
 
 template <int G>
-void launch_gather(Variant v, const conv_plan *plan, const float *x, float *y, int batch, hipStream_t q) {
+void launch_gather(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, int batch, hipStream_t q) {
     const int rows = (int)plan->rows;
     const unsigned bx = (unsigned)(((int64_t)rows * G + kGatherThreads - 1) / kGatherThreads);
     auto by = [&](int per) { int b = batch / per; return (unsigned)(b > 65535 ? 65535 : b); };
-    switch (v) {
-        case Variant::GatherScalar:
+    switch (c.nv) {
+        case 0:
             spmm_gather_scalar_kernel<G><<<dim3(bx, by(1)), kGatherThreads, 0, q>>>(
                 plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch);
             break;
-        case Variant::GatherVec4:
+        case 1:
             spmm_gather_vec_kernel<G, 1><<<dim3(bx, by(4)), kGatherThreads, 0, q>>>(
                 plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch);
             break;
-        case Variant::GatherVec8:
+        case 2:
             spmm_gather_vec_kernel<G, 2><<<dim3(bx, by(8)), kGatherThreads, 0, q>>>(
                 plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch);
             break;
-        case Variant::GatherVec16:
+        default:
             spmm_gather_vec_kernel<G, 4><<<dim3(bx, by(16)), kGatherThreads, 0, q>>>(
                 plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch);
             break;
+    }
+}
+
+template <int NIT, int NV>
+bool launch_tile_inst(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    auto kern = spmm_tile_kernel<kTileG, NIT, NV>;
+    // more than 64 KiB of dynamic LDS has to be allowed once per kernel (and device)
+    static thread_local int allowed_dev[16];
+    static thread_local size_t allowed_lds[16];
+    int dev = plan->device & 15;
+    if (c.lds > 64 * 1024 && (allowed_dev[dev] != plan->device + 1 || allowed_lds[dev] < c.lds)) {
+        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu)))
+            return false;
+        allowed_dev[dev] = plan->device + 1;
+        allowed_lds[dev] = kLdsPerCu;
+    }
+    const dim3 grid((unsigned)(c.geom.tiles_per_xcd * kXcds), (unsigned)(c.geom.batch / (4 * NV)));
+    kern<<<grid, c.threads, c.lds, q>>>(plan->row_ptr, plan->col_idx, plan->vals, x, y, c.geom);
+    return true;
+}
+
+template <int NV>
+bool launch_tile_nv(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    switch (c.nit) {
+        case 2: return launch_tile_inst<2, NV>(c, plan, x, y, q);
+        case 4: return launch_tile_inst<4, NV>(c, plan, x, y, q);
+        case 7: return launch_tile_inst<7, NV>(c, plan, x, y, q);
+        case 11: return launch_tile_inst<11, NV>(c, plan, x, y, q);
+        default: return launch_tile_inst<16, NV>(c, plan, x, y, q);
+    }
+}
+
+bool launch_tile(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    switch (c.nv) {
+        case 1: return launch_tile_nv<1>(c, plan, x, y, q);
+        case 2: return launch_tile_nv<2>(c, plan, x, y, q);
+        default: return launch_tile_nv<4>(c, plan, x, y, q);
     }
 }
 
@@ -212,13 +320,17 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
         if (xb < ye && yb < xe) return CONV_EALIAS;
     }
     hipStream_t q = (hipStream_t)stream;
-    const Variant v = pick_variant(plan, x_dev, y_dev, batch);
-    switch (group_width(plan->max_row_nnz)) {
-        case 1: launch_gather<1>(v, plan, x_dev, y_dev, batch, q); break;
-        case 2: launch_gather<2>(v, plan, x_dev, y_dev, batch, q); break;
-        case 4: launch_gather<4>(v, plan, x_dev, y_dev, batch, q); break;
-        case 8: launch_gather<8>(v, plan, x_dev, y_dev, batch, q); break;
-        default: launch_gather<16>(v, plan, x_dev, y_dev, batch, q); break;
+    const ApplyChoice c = choose_apply(plan, x_dev, y_dev, batch);
+    if (c.kind == Kind::Tile) {
+        if (!launch_tile(c, plan, x_dev, y_dev, q)) return CONV_EHIP;
+    } else {
+        switch (c.g) {
+            case 1: launch_gather<1>(c, plan, x_dev, y_dev, batch, q); break;
+            case 2: launch_gather<2>(c, plan, x_dev, y_dev, batch, q); break;
+            case 4: launch_gather<4>(c, plan, x_dev, y_dev, batch, q); break;
+            case 8: launch_gather<8>(c, plan, x_dev, y_dev, batch, q); break;
+            default: launch_gather<16>(c, plan, x_dev, y_dev, batch, q); break;
+        }
     }
     if (!hip_ok(hipGetLastError())) return CONV_EHIP;
     return CONV_OK;
@@ -240,7 +352,16 @@ int conv_plan_shape(const conv_plan *plan, int *m, int *n, int *k, int *s, int *
 
 const char *conv_spmv_variant(const conv_plan *plan, int batch) {
     if (!plan || batch < 1) return nullptr;
-    return variant_name(pick_variant(plan, nullptr, nullptr, batch));
+    static thread_local char name[96];
+    const ApplyChoice c = choose_apply(plan, nullptr, nullptr, batch);
+    switch (c.kind) {
+        case Kind::GatherScalar: snprintf(name, sizeof name, "gather_g%d_scalar", c.g); break;
+        case Kind::GatherVec: snprintf(name, sizeof name, "gather_g%d_float4x%d", c.g, c.nv); break;
+        case Kind::Tile:
+            snprintf(name, sizeof name, "lds_tile_%dx%d_g%d_nit%d_float4x%d", c.geom.th, c.geom.tw, c.g, c.nit, c.nv);
+            break;
+    }
+    return name;
 }
 
 int conv_plan_destroy(conv_plan *plan) {
