@@ -16,9 +16,13 @@
 // holds the finished columns [l*4*NV/G, (l+1)*4*NV/G) and the wave stores
 // 64/G complete, contiguous y rows.
 //
-// The kernel stays a CSR product: a stored column is located in the LDS tile
-// by arithmetic on its value, and a column that falls outside the tile is
-// read from global memory instead.
+// The entry loads of pass i+1 are issued before the arithmetic of pass i
+// (two register sets used alternately), and the arithmetic of a pass is one
+// straight-line block: a lane whose slot is past the end of its row, or whose
+// stored column is not in the staged window, reads a zero pixel kept in LDS
+// with weight 0.  The kernel stays a CSR product: a stored column is located
+// in the LDS tile by arithmetic on its value, and any column that falls
+// outside the tile is picked up afterwards from global memory.
 #pragma once
 #include "device_util.h"
 
@@ -27,11 +31,11 @@ namespace convspmv {
 struct TileGeom {
     int m, n, m_out, n_out, s, p;
     int batch;            // x / y row pitch, in floats
-    int th, tw;           // output tile: th lines of tw pixels (tw a multiple of 64/G)
+    int nnz;
+    int th;               // output lines per tile (pixels per line: template TW)
     int tiles_x, tiles_y, n_tiles, tiles_per_xcd;
-    int ih, iw;           // input extent a full tile can touch: (th-1)*s+k, (tw-1)*s+k
-    int iw_pitch;         // LDS pixels per input line (>= iw)
-    int chunk_stride;     // LDS pixels between the planes of successive float4 column chunks (>= ih*iw_pitch)
+    int ih, iw;           // input extent a full tile can touch: (th-1)*s+k, (TW-1)*s+k
+    int iw_pitch;         // LDS pixels per input line (>= iw); ih*iw_pitch < CS (template)
     float inv_n;          // 1.0f / n
 };
 
@@ -60,17 +64,31 @@ constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
 constexpr int imax(int a, int b) { return a > b ? a : b; }
 
 // Non-temporal 4-byte loads for the entry stream (used once, keep it out of
-// the way of x in the caches).
-__device__ __forceinline__ int stream_load(const int *p) { return __builtin_nontemporal_load(p); }
-__device__ __forceinline__ float stream_load(const float *p) { return __builtin_nontemporal_load(p); }
+// the way of x in the caches); base is wave-uniform, off a byte offset.
+__device__ __forceinline__ int stream_load_i(const int *base, unsigned off) {
+    return __builtin_nontemporal_load(reinterpret_cast<const int *>(reinterpret_cast<const char *>(base) + off));
+}
+__device__ __forceinline__ float stream_load_f(const float *base, unsigned off) {
+    return __builtin_nontemporal_load(reinterpret_cast<const float *>(reinterpret_cast<const char *>(base) + off));
+}
 
-template <int G, int NIT, int NV>
-__global__ __launch_bounds__(512) void spmm_tile_kernel(const int *__restrict__ row_ptr,
-                                                        const int *__restrict__ col_idx,
-                                                        const float *__restrict__ vals,
-                                                        const float *__restrict__ x, float *__restrict__ y,
-                                                        TileGeom g) {
+// floor(a / d) as in div_small, with the +0.5 folded into one fused
+// multiply-add: a*inv + 0.5*inv is the same real number as (a + 0.5)*inv and is
+// rounded once.
+__device__ __forceinline__ int div_small_fma(int a, float inv, float half_inv) {
+    return (int)fmaf((float)a, inv, half_inv);
+}
+
+// CS: LDS pixels per plane (one plane per float4 column chunk), a compile-time
+// constant so that the NV reads of a pixel differ only by an immediate offset.
+template <int G, int NIT, int NV, int TW, int CS>
+__global__ __launch_bounds__(TW * 8) void spmm_tile_kernel(const int *__restrict__ row_ptr,
+                                                           const int *__restrict__ col_idx,
+                                                           const float *__restrict__ vals,
+                                                           const float *__restrict__ x, float *__restrict__ y,
+                                                           TileGeom g) {
     constexpr int RW = kWave / G;        // rows per wave pass
+    constexpr int GPL = TW / RW;         // wave passes per output line of the tile
     constexpr int NVAL = 4 * NV;         // batch columns per lane
     // The combine runs log2(G) steps; the first SCAT of them halve the value
     // count (reduce-scatter), any left over are plain pair sums.
@@ -78,17 +96,18 @@ __global__ __launch_bounds__(512) void spmm_tile_kernel(const int *__restrict__ 
     constexpr int CNT = NVAL >> SCAT;             // finished columns per storing lane
     constexpr int DUP = ilog2(G) - SCAT;          // low lane bits that end up with copies
     static_assert(G == 4 || G == 8 || G == 16, "group width");
+    static_assert(TW % RW == 0, "a wave pass must not straddle two output lines");
     extern __shared__ float4 smem[];
     float4 *xs = smem;
-    int *rp_s = reinterpret_cast<int *>(smem + (size_t)NV * g.chunk_stride);
+    int *rp_s = reinterpret_cast<int *>(smem + (size_t)NV * CS);
 
     // ---- which tile (XCD-aware: each XCD walks one contiguous band of tiles)
     const int local = blockIdx.x / kXcds;
     const int tile = (blockIdx.x % kXcds) * g.tiles_per_xcd + local;
     if (tile >= g.n_tiles) return;       // uniform over the block
     const int ty = tile / g.tiles_x, tx = tile - ty * g.tiles_x;
-    const int x0 = ty * g.th, y0 = tx * g.tw;
-    const int thc = min(g.th, g.m_out - x0), twc = min(g.tw, g.n_out - y0);
+    const int x0 = ty * g.th, y0 = tx * TW;
+    const int thc = min(g.th, g.m_out - x0), twc = min(TW, g.n_out - y0);
     const int c0 = blockIdx.y * NVAL;
 
     // ---- input window of the tile, clipped to the image
@@ -97,6 +116,7 @@ __global__ __launch_bounds__(512) void spmm_tile_kernel(const int *__restrict__ 
     const int ihc = max(min(i_lo + g.ih, g.m) - i0, 0);
     const int iwc = max(min(j_lo + g.iw, g.n) - j0, 0);
     const int cbase = i0 * g.n + j0;
+    const int zslot = g.ih * g.iw_pitch;          // a pixel of zeros in every plane
     const int nthreads = blockDim.x, tid = threadIdx.x;
 
     {   // x window -> LDS, plane v holds columns [c0 + 4v, c0 + 4v + 4) of every pixel
@@ -108,12 +128,13 @@ __global__ __launch_bounds__(512) void spmm_tile_kernel(const int *__restrict__ 
             const int di = div_small(q, inv_iwc), dj = q - di * iwc;
             const float4 *src = reinterpret_cast<const float4 *>(
                 x + ((long long)(i0 + di) * g.n + (j0 + dj)) * g.batch + c0);
-            xs[v * g.chunk_stride + di * g.iw_pitch + dj] = src[v];
+            xs[v * CS + di * g.iw_pitch + dj] = src[v];
         }
-        // row_ptr of the tile: tw + 1 values per output line
-        const int rp_items = g.th * (g.tw + 1);
+        if (tid < NV) xs[tid * CS + zslot] = make_float4(0.f, 0.f, 0.f, 0.f);
+        // row_ptr of the tile: TW + 1 values per output line
+        const int rp_items = g.th * (TW + 1);
         for (int item = tid; item < rp_items; item += nthreads) {
-            const int line = item / (g.tw + 1), yy = item - line * (g.tw + 1);
+            const int line = item / (TW + 1), yy = item - line * (TW + 1);
             int v = 0;
             if (line < thc && yy <= twc) v = row_ptr[(long long)(x0 + line) * g.n_out + y0 + yy];
             rp_s[item] = v;
@@ -121,76 +142,102 @@ __global__ __launch_bounds__(512) void spmm_tile_kernel(const int *__restrict__ 
     }
     __syncthreads();
 
-    const int lane = tid % kWave, wave = tid / kWave, nwaves = nthreads / kWave;
+    const int lane = tid % kWave;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int gl = lane % G, gr = lane / G;
-    const int groups_per_line = g.tw / RW;
-    const int npass = g.th * groups_per_line;
-    const unsigned lim = (unsigned)(ihc * g.n);      // deltas below this are on a tile line
+    const unsigned lim = (unsigned)(ihc * g.n);      // deltas below this are on a line of the window
+    const float half_inv_n = 0.5f * g.inv_n;
 
-    int cur_c[NIT], nxt_c[NIT];
-    float cur_v[NIT], nxt_v[NIT];
-    int beg = 0, end = 0, nbeg = 0, nend = 0;
-
-    auto bounds = [&](int pid, int &b, int &e) {
-        const int line = pid / groups_per_line, yy = (pid - line * groups_per_line) * RW + gr;
-        b = e = 0;
-        if (line < thc && yy < twc) {
-            b = rp_s[line * (g.tw + 1) + yy];
-            e = rp_s[line * (g.tw + 1) + yy + 1];
-        }
+    struct Pass {
+        int c[NIT];
+        float v[NIT];
+        int beg, end;
     };
-    auto fetch = [&](int b, int e, int (&c)[NIT], float (&v)[NIT]) {
+
+    // Row bounds of this lane's row in pass pid and the entry loads for it.
+    auto fetch = [&](int pid, Pass &ps) {
+        const int line = pid / GPL, yy0 = (pid % GPL) * RW;          // wave-uniform
+        const int yy = yy0 + gr;
+        const int *rp_line = rp_s + line * (TW + 1);
+        ps.beg = ps.end = 0;
+        if (line < thc && yy < twc) {
+            ps.beg = rp_line[yy];
+            ps.end = rp_line[yy + 1];
+        }
+        // wave-uniform base: first entry of the tile line; lane offsets from it stay small
+        const int line_base = __builtin_amdgcn_readfirstlane(rp_line[0]);
+        const int span_end = __builtin_amdgcn_readfirstlane(rp_line[min(yy0 + RW, twc)]);
+        const int *cb = col_idx + line_base;
+        const float *vb = vals + line_base;
+        const unsigned off = (unsigned)(max(ps.beg - line_base, 0) + gl) * 4u;
+        // Both branches issue exactly 2*NIT loads and contain no lane-dependent
+        // control flow, so the number of loads in flight is the same on every
+        // path and later waits can leave the newest pass outstanding.
+        if (line < thc && (long long)span_end + NIT * G <= g.nnz) {
+            // every slot of every lane lies inside the arrays: slots past the end of
+            // a row fetch entries of later rows, which the arithmetic ignores
 #pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int idx = b + gl + it * G;
-            c[it] = 0;
-            v[it] = 0.0f;
-            if (idx < e) {
-                c[it] = stream_load(col_idx + idx);
-                v[it] = stream_load(vals + idx);
+            for (int it = 0; it < NIT; ++it) {
+                ps.c[it] = stream_load_i(cb, off + it * G * 4);
+                ps.v[it] = stream_load_f(vb, off + it * G * 4);
+            }
+        } else {
+            // the last rows of T (or a tile line below the image): clamp to the last entry
+            const unsigned last = (unsigned)(g.nnz - 1 - line_base) * 4u;
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                const unsigned o = min(off + it * G * 4, last);
+                ps.c[it] = stream_load_i(cb, o);
+                ps.v[it] = stream_load_f(vb, o);
             }
         }
     };
 
-    int pid = wave;
-    if (pid < npass) {
-        bounds(pid, beg, end);
-        fetch(beg, end, cur_c, cur_v);
-    }
-    for (; pid < npass; pid += nwaves) {
-        const int npid = pid + nwaves;
-        if (npid < npass) {              // uniform over the wave
-            bounds(npid, nbeg, nend);
-            fetch(nbeg, nend, nxt_c, nxt_v);
-        }
-
+    auto compute = [&](int pid, const Pass &ps) {
         float acc[NVAL];
 #pragma unroll
         for (int i = 0; i < NVAL; ++i) acc[i] = 0.0f;
+        bool stray = false;              // an in-row entry whose column is outside the window
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
-            if (beg + gl + it * G < end) {
-                const int col = cur_c[it];
-                const float w = cur_v[it];
-                const int delta = col - cbase;
-                const int di = div_small(delta, g.inv_n);
-                const int dj = delta - di * g.n;
-                float4 xv[NV];
-                if ((unsigned)delta < lim && (unsigned)dj < (unsigned)iwc) {
-                    const float4 *src = xs + (di * g.iw_pitch + dj);
+            const bool act = ps.beg + gl + it * G < ps.end;
+            const int delta = ps.c[it] - cbase;
+            const int di = div_small_fma(delta, g.inv_n, half_inv_n);
+            const int dj = delta - __mul24(di, g.n);
+            const bool in = (unsigned)delta < lim && (unsigned)dj < (unsigned)iwc;
+            stray |= act && !in;
+            const int pix = (act && in) ? __mul24(di, g.iw_pitch) + dj : zslot;
+            const float w = (act && in) ? ps.v[it] : 0.0f;
+            const float4 *src = xs + pix;
 #pragma unroll
-                    for (int v = 0; v < NV; ++v) xv[v] = src[v * g.chunk_stride];
-                } else {                 // stored column outside the staged window
-                    const float4 *src = reinterpret_cast<const float4 *>(x + (long long)col * g.batch + c0);
+            for (int v = 0; v < NV; ++v) {
+                const float4 xv = src[v * CS];
+                acc[4 * v + 0] = fmaf(w, xv.x, acc[4 * v + 0]);
+                acc[4 * v + 1] = fmaf(w, xv.y, acc[4 * v + 1]);
+                acc[4 * v + 2] = fmaf(w, xv.z, acc[4 * v + 2]);
+                acc[4 * v + 3] = fmaf(w, xv.w, acc[4 * v + 3]);
+            }
+        }
+        if (__builtin_expect(__any(stray), 0)) {
+            // cold: some stored column is not in the staged window; take those from global memory
 #pragma unroll
-                    for (int v = 0; v < NV; ++v) xv[v] = src[v];
-                }
+            for (int it = 0; it < NIT; ++it) {
+                const bool act = ps.beg + gl + it * G < ps.end;
+                const int delta = ps.c[it] - cbase;
+                const int di = div_small_fma(delta, g.inv_n, half_inv_n);
+                const int dj = delta - __mul24(di, g.n);
+                const bool in = (unsigned)delta < lim && (unsigned)dj < (unsigned)iwc;
+                if (act && !in) {
+                    const float4 *src = reinterpret_cast<const float4 *>(x + (long long)ps.c[it] * g.batch + c0);
+                    const float w = ps.v[it];
 #pragma unroll
-                for (int v = 0; v < NV; ++v) {
-                    acc[4 * v + 0] = fmaf(w, xv[v].x, acc[4 * v + 0]);
-                    acc[4 * v + 1] = fmaf(w, xv[v].y, acc[4 * v + 1]);
-                    acc[4 * v + 2] = fmaf(w, xv[v].z, acc[4 * v + 2]);
-                    acc[4 * v + 3] = fmaf(w, xv[v].w, acc[4 * v + 3]);
+                    for (int v = 0; v < NV; ++v) {
+                        const float4 xv = src[v];
+                        acc[4 * v + 0] = fmaf(w, xv.x, acc[4 * v + 0]);
+                        acc[4 * v + 1] = fmaf(w, xv.y, acc[4 * v + 1]);
+                        acc[4 * v + 2] = fmaf(w, xv.z, acc[4 * v + 2]);
+                        acc[4 * v + 3] = fmaf(w, xv.w, acc[4 * v + 3]);
+                    }
                 }
             }
         }
@@ -210,30 +257,44 @@ __global__ __launch_bounds__(512) void spmm_tile_kernel(const int *__restrict__ 
             combine_step<imax(NVAL / 2, 1), kDppXor1>(acc, (gl & 1) != 0);
         }
 
-        {   // lanes whose DUP low bits are clear hold CNT finished columns of their row,
-            // starting at column (gl >> DUP) * CNT of this launch's column block
-            const int line = pid / groups_per_line, yy = (pid - line * groups_per_line) * RW + gr;
-            if (line < thc && yy < twc && (gl & ((1 << DUP) - 1)) == 0) {
-                float *dst = y + ((long long)(x0 + line) * g.n_out + (y0 + yy)) * g.batch + c0 + (gl >> DUP) * CNT;
-                if constexpr (CNT == 1) {
-                    dst[0] = acc[0];
-                } else if constexpr (CNT == 2) {
-                    *reinterpret_cast<float2 *>(dst) = make_float2(acc[0], acc[1]);
-                } else {
+        // lanes whose DUP low bits are clear hold CNT finished columns of their row,
+        // starting at column (gl >> DUP) * CNT of this launch's column block
+        const int line = pid / GPL, yy = (pid % GPL) * RW + gr;
+        if (line < thc && yy < twc && (gl & ((1 << DUP) - 1)) == 0) {
+            float *dst = y + ((long long)(x0 + line) * g.n_out + (y0 + yy)) * g.batch + c0 + (gl >> DUP) * CNT;
+            if constexpr (CNT == 1) {
+                dst[0] = acc[0];
+            } else if constexpr (CNT == 2) {
+                *reinterpret_cast<float2 *>(dst) = make_float2(acc[0], acc[1]);
+            } else {
 #pragma unroll
-                    for (int i = 0; i < CNT; i += 4)
-                        *reinterpret_cast<float4 *>(dst + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
-                }
+                for (int i = 0; i < CNT; i += 4)
+                    *reinterpret_cast<float4 *>(dst + i) = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
             }
         }
+    };
 
-        beg = nbeg;
-        end = nend;
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            cur_c[it] = nxt_c[it];
-            cur_v[it] = nxt_v[it];
-        }
+    // ---- this wave takes pass wave of every tile line (the block has GPL
+    // waves).  Two register sets alternate so that the loads of the next pass
+    // are in flight during the arithmetic of this one; the steady-state loop
+    // fetches unconditionally.
+    if (wave >= GPL) return;             // launched with more waves than passes per line
+    const int nline = g.th;
+    Pass pa, pb;
+    fetch(wave, pa);
+    int i = 0;
+    for (; i + 2 < nline; i += 2) {
+        fetch(wave + (i + 1) * GPL, pb);
+        compute(wave + i * GPL, pa);
+        fetch(wave + (i + 2) * GPL, pa);
+        compute(wave + (i + 1) * GPL, pb);
+    }
+    if (nline - i == 2) {
+        fetch(wave + (i + 1) * GPL, pb);
+        compute(wave + i * GPL, pa);
+        compute(wave + (i + 1) * GPL, pb);
+    } else {
+        compute(wave + i * GPL, pa);
     }
 }
 

@@ -157,6 +157,7 @@ struct ApplyChoice {
     int g;          // lanes per row
     int nit;        // entries per lane (tile kernel: compile-time trip count)
     int nv;         // float4 column chunks per lane (0 = scalar columns)
+    int tw;         // tile kernel: output pixels per tile line
     int threads;
     size_t lds;
     TileGeom geom;
@@ -174,36 +175,47 @@ constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr int kTileG = 8;
 const int kTileNit[] = {2, 4, 7, 11, 16};
 
-// Tile shapes tried in order: {output lines, output pixels per line, threads}.
-const int kTileShapes[][3] = {{8, 64, 512}, {8, 32, 256}, {4, 32, 128}, {2, 32, 64}};
+// Tile kernel instantiations: output pixels per tile line (threads = 8 * TW)
+// and LDS pixels per column-chunk plane.  The plane size is 4 mod 16 so that
+// the four planes start 16 banks apart.
+constexpr int kTileWide = 64, kPlaneWide = 1028;
+constexpr int kTileNarrow = 32, kPlaneNarrow = 516;
 
 int round_up_mod(int v, int mod, int rem) {      // smallest r >= v with r % mod == rem
     int r = v - (v % mod) + rem;
     return r < v ? r + mod : r;
 }
 
-bool tile_geometry(const conv_plan *plan, int batch, int nv, int th, int tw, TileGeom *out, size_t *lds) {
+// Geometry of a tile kernel launch: the widest line pitch rule and the most
+// output lines per tile whose input window still fits one LDS plane.
+bool tile_geometry(const conv_plan *plan, int batch, int tw, int plane, TileGeom *out) {
     const ConvShape &sh = plan->shape;
     TileGeom g{};
     g.m = sh.m; g.n = sh.n; g.m_out = sh.m_out; g.n_out = sh.n_out; g.s = sh.s; g.p = sh.p;
     g.batch = batch;
-    g.th = th; g.tw = tw;
+    g.nnz = (int)plan->nnz;
+    const int64_t iw = (int64_t)(tw - 1) * sh.s + sh.k;
+    if (iw + 16 > plane) return false;
+    g.iw = (int)iw;
+    g.iw_pitch = round_up_mod((int)iw, 16, 8);
+    // lines of input that fit: ih * iw_pitch + 1 <= plane (one pixel of zeros follows the window)
+    const int64_t ih_max = (plane - 1) / g.iw_pitch;
+    if (ih_max < sh.k) return false;
+    int64_t th = (ih_max - sh.k) / sh.s + 1;
+    if (th > 8) th = 8;
+    if (th > sh.m_out) th = sh.m_out;
+    const int64_t ih = (th - 1) * sh.s + sh.k;
+    g.th = (int)th;
+    g.ih = (int)ih;
     g.tiles_x = (sh.n_out + tw - 1) / tw;
-    g.tiles_y = (sh.m_out + th - 1) / th;
+    g.tiles_y = (int)((sh.m_out + th - 1) / th);
     const int64_t n_tiles = (int64_t)g.tiles_x * g.tiles_y;
-    const int64_t ih = (int64_t)(th - 1) * sh.s + sh.k, iw = (int64_t)(tw - 1) * sh.s + sh.k;
     // int arithmetic in the kernel: s*x0 - p, i_lo + ih, ihc * n (float-reciprocal division needs < 2^21)
     if ((int64_t)sh.m + 2LL * sh.p + ih >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + iw >= (1LL << 30)) return false;
     if (ih * sh.n >= (1LL << 21) || n_tiles + kXcds >= (1LL << 31) / kXcds) return false;
     g.n_tiles = (int)n_tiles;
     g.tiles_per_xcd = (int)((n_tiles + kXcds - 1) / kXcds);
-    g.ih = (int)ih; g.iw = (int)iw;
-    g.iw_pitch = round_up_mod((int)iw, 16, 8);
-    const int64_t plane = ih * g.iw_pitch;
-    if (plane * nv >= (1LL << 21)) return false;
-    g.chunk_stride = round_up_mod((int)plane, 16, 4);
     g.inv_n = 1.0f / (float)sh.n;
-    *lds = (size_t)nv * g.chunk_stride * 16 + (size_t)th * (tw + 1) * 4;
     *out = g;
     return true;
 }
@@ -221,23 +233,24 @@ ApplyChoice choose_apply(const conv_plan *plan, const float *x, const float *y, 
     c.nv = batch % 16 == 0 ? 4 : (batch % 8 == 0 ? 2 : 1);
     c.kind = Kind::GatherVec;
     c.threads = kGatherThreads;
-    // LDS-tiled kernel when the rows fit its unrolled trip count and a tile
-    // leaves room for two workgroups per CU
+    // LDS-tiled kernel when the rows fit its unrolled trip count and the
+    // input window of at least one output line fits the LDS planes
     const int need = (plan->max_row_nnz + kTileG - 1) / kTileG;
     int nit = 0;
     for (int cand : kTileNit)
         if (cand >= need) { nit = cand; break; }
-    if (nit == 0 || batch / (4 * c.nv) > 65535) return c;
-    for (const auto &shp : kTileShapes) {
+    if (nit == 0 || batch / (4 * c.nv) > 65535 || plan->nnz == 0) return c;
+    const int tws[2] = {kTileWide, kTileNarrow}, planes[2] = {kPlaneWide, kPlaneNarrow};
+    for (int i = 0; i < 2; ++i) {
         TileGeom g;
-        size_t lds;
-        if (!tile_geometry(plan, batch, c.nv, shp[0], shp[1], &g, &lds)) continue;
-        if (lds > kLdsPerCu / 2) continue;
+        if (plan->shape.n_out <= kTileNarrow && tws[i] == kTileWide) continue;
+        if (!tile_geometry(plan, batch, tws[i], planes[i], &g)) continue;
         c.kind = Kind::Tile;
         c.g = kTileG;
         c.nit = nit;
-        c.threads = shp[2];
-        c.lds = lds;
+        c.tw = tws[i];
+        c.threads = tws[i] * 8;
+        c.lds = (size_t)c.nv * planes[i] * 16 + (size_t)g.th * (tws[i] + 1) * 4;
         c.geom = g;
         break;
     }
@@ -269,33 +282,37 @@ void launch_gather(const ApplyChoice &c, const conv_plan *plan, const float *x, 
     }
 }
 
-template <int NIT, int NV>
+template <int NIT, int NV, int TW, int CS>
 bool launch_tile_inst(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
-    auto kern = spmm_tile_kernel<kTileG, NIT, NV>;
-    // more than 64 KiB of dynamic LDS has to be allowed once per kernel (and device)
-    static thread_local int allowed_dev[16];
-    static thread_local size_t allowed_lds[16];
-    int dev = plan->device & 15;
-    if (c.lds > 64 * 1024 && (allowed_dev[dev] != plan->device + 1 || allowed_lds[dev] < c.lds)) {
+    auto kern = spmm_tile_kernel<kTileG, NIT, NV, TW, CS>;
+    // more than 64 KiB of dynamic LDS has to be allowed once per kernel and device
+    static thread_local bool allowed[64];
+    const int dev = plan->device;
+    if (c.lds > 64 * 1024 && (dev < 0 || dev >= 64 || !allowed[dev])) {
         if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsPerCu)))
             return false;
-        allowed_dev[dev] = plan->device + 1;
-        allowed_lds[dev] = kLdsPerCu;
+        if (dev >= 0 && dev < 64) allowed[dev] = true;
     }
     const dim3 grid((unsigned)(c.geom.tiles_per_xcd * kXcds), (unsigned)(c.geom.batch / (4 * NV)));
     kern<<<grid, c.threads, c.lds, q>>>(plan->row_ptr, plan->col_idx, plan->vals, x, y, c.geom);
     return true;
 }
 
+template <int NIT, int NV>
+bool launch_tile_tw(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    if (c.tw == kTileWide) return launch_tile_inst<NIT, NV, kTileWide, kPlaneWide>(c, plan, x, y, q);
+    return launch_tile_inst<NIT, NV, kTileNarrow, kPlaneNarrow>(c, plan, x, y, q);
+}
+
 template <int NV>
 bool launch_tile_nv(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
     switch (c.nit) {
-        case 2: return launch_tile_inst<2, NV>(c, plan, x, y, q);
-        case 4: return launch_tile_inst<4, NV>(c, plan, x, y, q);
-        case 7: return launch_tile_inst<7, NV>(c, plan, x, y, q);
-        case 11: return launch_tile_inst<11, NV>(c, plan, x, y, q);
-        default: return launch_tile_inst<16, NV>(c, plan, x, y, q);
+        case 2: return launch_tile_tw<2, NV>(c, plan, x, y, q);
+        case 4: return launch_tile_tw<4, NV>(c, plan, x, y, q);
+        case 7: return launch_tile_tw<7, NV>(c, plan, x, y, q);
+        case 11: return launch_tile_tw<11, NV>(c, plan, x, y, q);
+        default: return launch_tile_tw<16, NV>(c, plan, x, y, q);
     }
 }
 
@@ -358,7 +375,7 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch) {
         case Kind::GatherScalar: snprintf(name, sizeof name, "gather_g%d_scalar", c.g); break;
         case Kind::GatherVec: snprintf(name, sizeof name, "gather_g%d_float4x%d", c.g, c.nv); break;
         case Kind::Tile:
-            snprintf(name, sizeof name, "lds_tile_%dx%d_g%d_nit%d_float4x%d", c.geom.th, c.geom.tw, c.g, c.nit, c.nv);
+            snprintf(name, sizeof name, "lds_tile_%dx%d_g%d_nit%d_float4x%d", c.geom.th, c.tw, c.g, c.nit, c.nv);
             break;
     }
     return name;
