@@ -63,13 +63,22 @@ __device__ __forceinline__ void combine_step(float (&a)[LEN], bool hi) {
 constexpr int ilog2(int v) { return v <= 1 ? 0 : 1 + ilog2(v / 2); }
 constexpr int imax(int a, int b) { return a > b ? a : b; }
 
-// Non-temporal 4-byte loads for the entry stream (used once, keep it out of
-// the way of x in the caches); base is wave-uniform, off a byte offset.
+// 4-byte loads of the entry stream; base is wave-uniform, off a byte offset.
+// Plain (temporal) loads on purpose: a group reads 32-byte pieces, so each
+// 128-byte line is touched by four consecutive loads of the same wave and has
+// to stay in the vector L1 between them.  With non-temporal loads every touch
+// became its own L2 request (measured: 85 % of L1 accesses went to L2 and the
+// kernel took 1.65x longer).
+#ifndef CONVSPMV_STREAM_NT
+#define CONVSPMV_STREAM_NT 0
+#endif
 __device__ __forceinline__ int stream_load_i(const int *base, unsigned off) {
-    return __builtin_nontemporal_load(reinterpret_cast<const int *>(reinterpret_cast<const char *>(base) + off));
+    const int *p = reinterpret_cast<const int *>(reinterpret_cast<const char *>(base) + off);
+    return CONVSPMV_STREAM_NT ? __builtin_nontemporal_load(p) : *p;
 }
 __device__ __forceinline__ float stream_load_f(const float *base, unsigned off) {
-    return __builtin_nontemporal_load(reinterpret_cast<const float *>(reinterpret_cast<const char *>(base) + off));
+    const float *p = reinterpret_cast<const float *>(reinterpret_cast<const char *>(base) + off);
+    return CONVSPMV_STREAM_NT ? __builtin_nontemporal_load(p) : *p;
 }
 
 // floor(a / d) as in div_small, with the +0.5 folded into one fused
