@@ -8,6 +8,7 @@
 #include <new>
 
 #include "apply_kernels.h"
+#include "apply_march_kernel.h"
 #include "apply_tile_kernel.h"
 #include "build_kernels.h"
 
@@ -150,7 +151,7 @@ namespace {
 // ---------------------------------------------------------------------------
 // Apply dispatch
 // ---------------------------------------------------------------------------
-enum class Kind { GatherScalar, GatherVec, Tile };
+enum class Kind { GatherScalar, GatherVec, Tile, March };
 
 struct ApplyChoice {
     Kind kind;
@@ -161,6 +162,8 @@ struct ApplyChoice {
     int threads;
     size_t lds;
     TileGeom geom;
+    int ls;         // march kernel: output lines per step
+    MarchGeom march;
 };
 
 // Lanes per row for the gather kernels: the narrowest power of two that keeps
@@ -212,11 +215,59 @@ bool tile_geometry(const conv_plan *plan, int batch, int tw, int plane, TileGeom
     const int64_t n_tiles = (int64_t)g.tiles_x * g.tiles_y;
     // int arithmetic in the kernel: s*x0 - p, i_lo + ih, ihc * n (float-reciprocal division needs < 2^21)
     if ((int64_t)sh.m + 2LL * sh.p + ih >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + iw >= (1LL << 30)) return false;
-    if (ih * sh.n >= (1LL << 21) || n_tiles + kXcds >= (1LL << 31) / kXcds) return false;
+    if (ih * sh.n >= (1LL << 21) || sh.n >= (1 << 20) || plan->cols > (1LL << 27)) return false;
+    if (n_tiles + kXcds >= (1LL << 31) / kXcds) return false;
     g.n_tiles = (int)n_tiles;
     g.tiles_per_xcd = (int)((n_tiles + kXcds - 1) / kXcds);
     g.inv_n = 1.0f / (float)sh.n;
     *out = g;
+    return true;
+}
+
+// Marching kernel: strips of kMarchTw output columns, a ring of kMarchNl input
+// lines in LDS, planes of kMarchLdsPixels / nv pixels per float4 column chunk.
+constexpr int kMarchTw = 64, kMarchNl = 16;
+constexpr int march_plane(int nv) { return nv == 4 ? 1156 : (nv == 2 ? 2308 : 4612); }   // 4 mod 16 each
+constexpr int kMarchTargetBlocks = 512;      // two resident workgroups on each of 256 CUs
+
+bool march_geometry(const conv_plan *plan, int batch, int nv, MarchGeom *out, int *ls_out) {
+    const ConvShape &sh = plan->shape;
+    MarchGeom g{};
+    g.m = sh.m; g.n = sh.n; g.m_out = sh.m_out; g.n_out = sh.n_out; g.s = sh.s; g.p = sh.p; g.k = sh.k;
+    g.batch = batch;
+    g.nnz = (int)plan->nnz;
+    const int64_t iw = (int64_t)(kMarchTw - 1) * sh.s + sh.k;
+    const int plane = march_plane(nv);
+    if (iw + 16 > plane) return false;
+    g.iw = (int)iw;
+    g.iw_pitch = round_up_mod((int)iw, 16, 8);
+    if ((int64_t)kMarchNl * g.iw_pitch + 1 > plane) return false;
+    // steps of two output lines when the ring and the per-thread line registers allow it
+    // (LS = 2 is built with 2 float4 per thread, LS = 1 with 4), else one line per step
+    const int threads = kMarchTw * 8;
+    int ls = 0;
+    if ((int64_t)sh.s * 3 + sh.k <= kMarchNl && 2LL * sh.s * iw * nv <= 2LL * threads) ls = 2;
+    else if ((int64_t)sh.s + sh.k <= kMarchNl && (int64_t)sh.s * iw * nv <= 4LL * threads) ls = 1;
+    if (ls == 0) return false;
+    // int arithmetic in the kernel: s*x - p + k, col*16, d16 < 2^25 (see the kernel)
+    if ((int64_t)sh.m + 2LL * sh.p + sh.k >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + iw >= (1LL << 30)) return false;
+    if (plan->cols > (1LL << 27) || 2LL * kMarchNl * sh.n * 16 > (1LL << 25)) return false;
+    if (sh.n_out < kMarchTw / 2) return false;          // a strip would be mostly empty
+    g.strips = (sh.n_out + kMarchTw - 1) / kMarchTw;
+    const int col_blocks = batch / (4 * nv);
+    int64_t segs = kMarchTargetBlocks / ((int64_t)g.strips * col_blocks);
+    if (segs < 1) segs = 1;
+    int64_t seg = (sh.m_out + segs - 1) / segs;
+    if (seg < 8) seg = 8;
+    seg = (seg + 1) & ~1LL;
+    g.seg = (int)seg;
+    g.segs = (int)((sh.m_out + seg - 1) / seg);
+    const int64_t jobs = (int64_t)g.strips * g.segs;
+    if (jobs + kXcds >= (1LL << 31) / kXcds) return false;
+    g.blocks_per_xcd = (int)((jobs + kXcds - 1) / kXcds);
+    g.inv_n = 1.0f / (float)sh.n;
+    *out = g;
+    *ls_out = ls;
     return true;
 }
 
@@ -240,6 +291,21 @@ ApplyChoice choose_apply(const conv_plan *plan, const float *x, const float *y, 
     for (int cand : kTileNit)
         if (cand >= need) { nit = cand; break; }
     if (nit == 0 || batch / (4 * c.nv) > 65535 || plan->nnz == 0) return c;
+    {
+        MarchGeom mg;
+        int ls;
+        if (march_geometry(plan, batch, c.nv, &mg, &ls)) {
+            c.kind = Kind::March;
+            c.g = kTileG;
+            c.nit = nit;
+            c.tw = kMarchTw;
+            c.threads = kMarchTw * 8;
+            c.lds = (size_t)c.nv * march_plane(c.nv) * 16;
+            c.ls = ls;
+            c.march = mg;
+            return c;
+        }
+    }
     const int tws[2] = {kTileWide, kTileNarrow}, planes[2] = {kPlaneWide, kPlaneNarrow};
     for (int i = 0; i < 2; ++i) {
         TileGeom g;
@@ -324,6 +390,52 @@ bool launch_tile(const ApplyChoice &c, const conv_plan *plan, const float *x, fl
     }
 }
 
+template <typename Kern>
+bool allow_large_lds(Kern kern, size_t lds, int dev, bool (&allowed)[64]) {
+    // more than 64 KiB of dynamic LDS has to be allowed once per kernel and device
+    if (lds <= 64 * 1024 || (dev >= 0 && dev < 64 && allowed[dev])) return true;
+    if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)kLdsPerCu)))
+        return false;
+    if (dev >= 0 && dev < 64) allowed[dev] = true;
+    return true;
+}
+
+template <int NIT, int NV, int LS, int XLD>
+bool launch_march_inst(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    auto kern = spmm_march_kernel<kTileG, NIT, NV, kMarchTw, kMarchNl, LS, XLD, march_plane(NV)>;
+    static thread_local bool allowed[64];
+    if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
+    const dim3 grid((unsigned)(c.march.blocks_per_xcd * kXcds), (unsigned)(c.march.batch / (4 * NV)));
+    kern<<<grid, c.threads, c.lds, q>>>(plan->row_ptr, plan->col_idx, plan->vals, x, y, c.march);
+    return true;
+}
+
+template <int NIT, int NV>
+bool launch_march_ls(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    if (c.ls == 2) return launch_march_inst<NIT, NV, 2, 2>(c, plan, x, y, q);
+    return launch_march_inst<NIT, NV, 1, 4>(c, plan, x, y, q);
+}
+
+template <int NV>
+bool launch_march_nv(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    switch (c.nit) {
+        case 2: return launch_march_ls<2, NV>(c, plan, x, y, q);
+        case 4: return launch_march_ls<4, NV>(c, plan, x, y, q);
+        case 7: return launch_march_ls<7, NV>(c, plan, x, y, q);
+        case 11: return launch_march_ls<11, NV>(c, plan, x, y, q);
+        default: return launch_march_ls<16, NV>(c, plan, x, y, q);
+    }
+}
+
+bool launch_march(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    switch (c.nv) {
+        case 1: return launch_march_nv<1>(c, plan, x, y, q);
+        case 2: return launch_march_nv<2>(c, plan, x, y, q);
+        default: return launch_march_nv<4>(c, plan, x, y, q);
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -338,7 +450,9 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
     }
     hipStream_t q = (hipStream_t)stream;
     const ApplyChoice c = choose_apply(plan, x_dev, y_dev, batch);
-    if (c.kind == Kind::Tile) {
+    if (c.kind == Kind::March) {
+        if (!launch_march(c, plan, x_dev, y_dev, q)) return CONV_EHIP;
+    } else if (c.kind == Kind::Tile) {
         if (!launch_tile(c, plan, x_dev, y_dev, q)) return CONV_EHIP;
     } else {
         switch (c.g) {
@@ -374,6 +488,9 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch) {
     switch (c.kind) {
         case Kind::GatherScalar: snprintf(name, sizeof name, "gather_g%d_scalar", c.g); break;
         case Kind::GatherVec: snprintf(name, sizeof name, "gather_g%d_float4x%d", c.g, c.nv); break;
+        case Kind::March:
+            snprintf(name, sizeof name, "lds_march_%dx%d_step%d_g%d_nit%d_float4x%d", c.march.seg, c.tw, c.ls, c.g, c.nit, c.nv);
+            break;
         case Kind::Tile:
             snprintf(name, sizeof name, "lds_tile_%dx%d_g%d_nit%d_float4x%d", c.geom.th, c.tw, c.g, c.nit, c.nv);
             break;
