@@ -25,9 +25,13 @@
 // from its value, and an entry whose column is not among the resident lines
 // (possible only if the arrays were edited) is taken from global memory.
 #pragma once
+#include <type_traits>
+
 #include "apply_tile_kernel.h"
 
 namespace convspmv {
+
+typedef float vec4 __attribute__((ext_vector_type(4)));
 
 struct MarchGeom {
     int m, n, m_out, n_out, s, p, k;
@@ -42,18 +46,26 @@ struct MarchGeom {
     float inv_n;          // 1.0f / n
 };
 
-// NL: ring lines (power of two, >= s*(2*LS-1) + k).  LS: output lines per step
-// (1 or 2).  XLD: float4 registers per thread that carry the next step's input
-// lines.  CS: LDS pixels per column-chunk plane (> NL*iw_pitch).
+// NV: float4 column chunks per lane (NV planes in LDS, 4*NV batch columns per
+// launch column block), or 0 for one scalar column per launch column block
+// (SpMV: one plane of floats).  NL: ring lines (power of two, >= s*(2*LS-1) + k).
+// LS: output lines per step (1 or 2).  XLD: registers (float4, or float when
+// NV = 0) per thread that carry the next step's input lines.  CS: LDS pixels
+// per plane (> NL*iw_pitch).
 template <int G, int NIT, int NV, int TW, int NL, int LS, int XLD, int CS>
-__global__ __launch_bounds__(TW * 8, 4) void spmm_march_kernel(const int *__restrict__ row_ptr,
+__global__ __launch_bounds__(512, 4) void spmm_march_kernel(const int *__restrict__ row_ptr,
                                                             const int *__restrict__ col_idx,
                                                             const float *__restrict__ vals,
                                                             const float *__restrict__ x, float *__restrict__ y,
                                                             MarchGeom g) {
     constexpr int RW = kWave / G;        // rows per wave pass
-    constexpr int NVAL = 4 * NV;         // batch columns per lane
-    constexpr int NTHREADS = TW * 8;
+    constexpr bool SCALAR = NV == 0;
+    constexpr int NP = SCALAR ? 1 : NV;           // LDS planes
+    constexpr int NVAL = SCALAR ? 1 : 4 * NV;     // batch columns per lane
+    constexpr int SH = SCALAR ? 2 : 4;            // log2 of the LDS bytes per pixel and plane
+    constexpr int PIXB = 1 << SH;
+    using elem_t = typename std::conditional<SCALAR, float, vec4>::type;   // one pixel of one plane
+    constexpr int NTHREADS = 512;
     constexpr int SCAT = ilog2(G) < ilog2(NVAL) ? ilog2(G) : ilog2(NVAL);
     constexpr int CNT = NVAL >> SCAT;             // finished columns per storing lane
     constexpr int DUP = ilog2(G) - SCAT;          // low lane bits that end up with copies
@@ -61,7 +73,7 @@ __global__ __launch_bounds__(TW * 8, 4) void spmm_march_kernel(const int *__rest
     static_assert(NTHREADS / kWave == TW / RW, "one wave per group of RW columns");
     static_assert((NL & (NL - 1)) == 0 && (LS == 1 || LS == 2), "ring / step shape");
     extern __shared__ float4 smem[];
-    float4 *xs = smem;                   // [NV planes][CS pixels]; pixel (line i, column j) at (i % NL)*pitch + (j - j0)
+    elem_t *xs = reinterpret_cast<elem_t *>(smem);   // [NP planes][CS pixels]; pixel (line i, column j) at (i % NL)*pitch + (j - j0)
 
     // ---- which strip segment (XCD-aware: an XCD owns a band of output lines across all strips)
     const int local = blockIdx.x / kXcds;
@@ -88,15 +100,15 @@ __global__ __launch_bounds__(TW * 8, 4) void spmm_march_kernel(const int *__rest
 
     {   // lines of the first step -> LDS
         const int lo = line_lo(xa), hi = line_hi(xa, LS);
-        const int items = (hi - lo) * iwc * NV;
+        const int items = (hi - lo) * iwc * NP;
         for (int item = tid; item < items; item += NTHREADS) {
-            const int q = item / NV, v = item % NV;
+            const int q = item / NP, v = item % NP;
             const int dl = div_small(q, inv_iwc), dj = q - dl * iwc;
             const int i = lo + dl;
-            const float4 *src = reinterpret_cast<const float4 *>(x + ((long long)i * g.n + (j0 + dj)) * g.batch + c0);
+            const elem_t *src = reinterpret_cast<const elem_t *>(x + ((long long)i * g.n + (j0 + dj)) * g.batch + c0);
             xs[v * CS + (i & (NL - 1)) * g.iw_pitch + dj] = src[v];
         }
-        if (tid < NV) xs[tid * CS + zslot] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (tid < NP) xs[tid * CS + zslot] = elem_t(0.0f);
     }
     __syncthreads();
 
@@ -150,23 +162,33 @@ __global__ __launch_bounds__(TW * 8, 4) void spmm_march_kernel(const int *__rest
         }
     };
 
-    // Window state of the current step (wave-uniform).  Offsets are in bytes of LDS,
-    // 16 per pixel: d16 = 16 * (col - cbase) = 16 * (di * n + dj) for a column on line
-    // ibase + di at strip pixel dj; ibase is a multiple of NL, so the ring slot of the
-    // line is di % NL.  The host guarantees m*n <= 2^27 (col*16 fits an int) and
-    // 2*NL*n*16 <= 2^25, which keeps d16 exact in fp32 and the quotient by n exact
-    // after one fused multiply-add and a truncation.
-    const int n16 = g.n * 16, pitch16 = g.iw_pitch * 16, zslot16 = zslot * 16;
-    const unsigned iwc16 = (unsigned)iwc * 16u;
-    const float inv_n16 = g.inv_n * 0.0625f, half_inv_n = 0.5f * g.inv_n;
-    int cbase16 = 0, lo16 = 0;
-    unsigned span16 = 0;
+    // Window state of the current step (wave-uniform).  Offsets are in bytes of LDS
+    // (PIXB per pixel, the suffix B below): dB = PIXB * (col - cbase) = PIXB * (di * n + dj)
+    // for a column on line ibase + di at strip pixel dj; ibase is a multiple of NL, so the
+    // ring slot of the line is di % NL.  The host guarantees m*n <= 2^27 (col*16 fits an
+    // int) and 2*NL*n*16 <= 2^25, which keeps dB (a multiple of PIXB below 2^25) exact in
+    // fp32 and the quotient by n exact after one fused multiply-add and a truncation.
+    const int nB = g.n * PIXB, pitchB = g.iw_pitch * PIXB, zslotB = zslot * PIXB;
+    const unsigned iwcB = (unsigned)iwc * PIXB;
+    const float inv_nB = g.inv_n / (float)PIXB, half_inv_n = 0.5f * g.inv_n;
+    int cbaseB = 0, loB = 0;
+    unsigned spanB = 0;
     auto set_window = [&](int xo) {
         const int lo = line_lo(xo), hi = line_hi(xo, LS);
         const int ibase = lo & ~(NL - 1);
-        cbase16 = (ibase * g.n + j0) * 16;
-        lo16 = (lo - ibase) * n16;
-        span16 = (unsigned)(hi - lo) * (unsigned)n16;
+        cbaseB = (ibase * g.n + j0) * PIXB;
+        loB = (lo - ibase) * nB;
+        spanB = (unsigned)(hi - lo) * (unsigned)nB;
+    };
+    auto fma_elem = [](float *a, float wt, const elem_t &e) {
+        if constexpr (SCALAR) {
+            a[0] = fmaf(wt, e, a[0]);
+        } else {
+            a[0] = fmaf(wt, e.x, a[0]);
+            a[1] = fmaf(wt, e.y, a[1]);
+            a[2] = fmaf(wt, e.z, a[2]);
+            a[3] = fmaf(wt, e.w, a[3]);
+        }
     };
 
     auto compute = [&](int xo, const Pass &ps) {
@@ -180,22 +202,22 @@ __global__ __launch_bounds__(TW * 8, 4) void spmm_march_kernel(const int *__rest
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const bool act = it * G < rem;
-            const int d16 = (ps.c[it] << 4) - cbase16;
-            const int di = (int)fmaf((float)d16, inv_n16, half_inv_n);
-            const int dj16 = d16 - __mul24(di, n16);
-            const bool in = (unsigned)(d16 - lo16) < span16 && (unsigned)dj16 < iwc16;
+            const int dB = (ps.c[it] << SH) - cbaseB;
+            const int di = (int)fmaf((float)dB, inv_nB, half_inv_n);
+            const int djB = dB - __mul24(di, nB);
+            const bool in = (unsigned)(dB - loB) < spanB && (unsigned)djB < iwcB;
             stray |= act && !in;
-            addr[it] = (act && in) ? __mul24(di & (NL - 1), pitch16) + dj16 : zslot16;
+            addr[it] = (act && in) ? __mul24(di & (NL - 1), pitchB) + djB : zslotB;
             w[it] = (act && in) ? ps.v[it] : 0.0f;
         }
         // LDS reads run one entry ahead of the multiply-adds, and no further: the
         // scheduler is kept from hoisting all reads of a pass to its start, which
         // would cost 16 registers per entry.
-        float4 xv[2][NV];
-        auto read_x = [&](int it, float4 (&dst)[NV]) {
-            const float4 *src = reinterpret_cast<const float4 *>(reinterpret_cast<const char *>(xs) + addr[it]);
+        elem_t xv[2][NP];
+        auto read_x = [&](int it, elem_t (&dst)[NP]) {
+            const elem_t *src = reinterpret_cast<const elem_t *>(reinterpret_cast<const char *>(xs) + addr[it]);
 #pragma unroll
-            for (int v = 0; v < NV; ++v) dst[v] = src[v * CS];
+            for (int v = 0; v < NP; ++v) dst[v] = src[v * CS];
         };
         read_x(0, xv[0]);
 #pragma unroll
@@ -203,13 +225,7 @@ __global__ __launch_bounds__(TW * 8, 4) void spmm_march_kernel(const int *__rest
             if (it + 1 < NIT) read_x(it + 1, xv[(it + 1) & 1]);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                const float4 xq = xv[it & 1][v];
-                acc[4 * v + 0] = fmaf(w[it], xq.x, acc[4 * v + 0]);
-                acc[4 * v + 1] = fmaf(w[it], xq.y, acc[4 * v + 1]);
-                acc[4 * v + 2] = fmaf(w[it], xq.z, acc[4 * v + 2]);
-                acc[4 * v + 3] = fmaf(w[it], xq.w, acc[4 * v + 3]);
-            }
+            for (int v = 0; v < NP; ++v) fma_elem(acc + 4 * v, w[it], xv[it & 1][v]);
             __builtin_amdgcn_sched_barrier(0);
         }
         if (__builtin_expect(__any(stray), 0)) {
@@ -217,21 +233,14 @@ __global__ __launch_bounds__(TW * 8, 4) void spmm_march_kernel(const int *__rest
 #pragma unroll
             for (int it = 0; it < NIT; ++it) {
                 const bool act = it * G < rem;
-                const int d16 = (ps.c[it] << 4) - cbase16;
-                const int di = (int)fmaf((float)d16, inv_n16, half_inv_n);
-                const int dj16 = d16 - __mul24(di, n16);
-                const bool in = (unsigned)(d16 - lo16) < span16 && (unsigned)dj16 < iwc16;
+                const int dB = (ps.c[it] << SH) - cbaseB;
+                const int di = (int)fmaf((float)dB, inv_nB, half_inv_n);
+                const int djB = dB - __mul24(di, nB);
+                const bool in = (unsigned)(dB - loB) < spanB && (unsigned)djB < iwcB;
                 if (act && !in) {
-                    const float4 *src = reinterpret_cast<const float4 *>(x + (long long)ps.c[it] * g.batch + c0);
-                    const float w = ps.v[it];
+                    const elem_t *src = reinterpret_cast<const elem_t *>(x + (long long)ps.c[it] * g.batch + c0);
 #pragma unroll
-                    for (int v = 0; v < NV; ++v) {
-                        const float4 xv = src[v];
-                        acc[4 * v + 0] = fmaf(w, xv.x, acc[4 * v + 0]);
-                        acc[4 * v + 1] = fmaf(w, xv.y, acc[4 * v + 1]);
-                        acc[4 * v + 2] = fmaf(w, xv.z, acc[4 * v + 2]);
-                        acc[4 * v + 3] = fmaf(w, xv.w, acc[4 * v + 3]);
-                    }
+                    for (int v = 0; v < NP; ++v) fma_elem(acc + 4 * v, ps.v[it], src[v]);
                 }
             }
         }
@@ -263,19 +272,18 @@ __global__ __launch_bounds__(TW * 8, 4) void spmm_march_kernel(const int *__rest
     // ---- input lines of the next step: global -> registers now, registers -> LDS at the
     // end of the step.  Always XLD loads per thread (clamped addresses) so that the
     // number of loads in flight does not depend on the position in the image.
-    typedef float vec4 __attribute__((ext_vector_type(4)));
-    vec4 xr[XLD];
+    elem_t xr[XLD];
     int xdst[XLD];                       // LDS pixel index, or -1
     auto load_next_lines = [&](int xo_next) {
         const int lo = line_hi(xo_next - LS, LS), hi = line_hi(xo_next, LS);   // new lines [lo, hi)
-        const int items = xo_next < xb ? (hi - lo) * iwc * NV : 0;
+        const int items = xo_next < xb ? (hi - lo) * iwc * NP : 0;
 #pragma unroll
         for (int r = 0; r < XLD; ++r) {
             const int item = tid + r * NTHREADS;
-            const int q = item / NV, v = item % NV;
+            const int q = item / NP, v = item % NP;
             const int dl = div_small(q, inv_iwc), dj = min(q - dl * iwc, max(iwc - 1, 0));
             const int i = min(lo + dl, g.m - 1);
-            const vec4 *src = reinterpret_cast<const vec4 *>(x + ((long long)i * g.n + (j0 + dj)) * g.batch + c0);
+            const elem_t *src = reinterpret_cast<const elem_t *>(x + ((long long)i * g.n + (j0 + dj)) * g.batch + c0);
             xr[r] = src[v];
             xdst[r] = item < items ? v * CS + (i & (NL - 1)) * g.iw_pitch + dj : -1;
         }
@@ -283,7 +291,7 @@ __global__ __launch_bounds__(TW * 8, 4) void spmm_march_kernel(const int *__rest
     auto store_next_lines = [&]() {
 #pragma unroll
         for (int r = 0; r < XLD; ++r)
-            if (xdst[r] >= 0) reinterpret_cast<vec4 *>(xs)[xdst[r]] = xr[r];
+            if (xdst[r] >= 0) xs[xdst[r]] = xr[r];
     };
 
     // ---- the march.  Output line xa + i is pass i of every wave; passes come in pairs

@@ -176,7 +176,7 @@ int group_width(int max_row_nnz) {
 
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr int kTileG = 8;
-const int kTileNit[] = {2, 4, 7, 11, 16};
+const int kTileNit[] = {2, 4, 7};       // trip counts the tile kernel is built for (8 lanes per row)
 
 // Tile kernel instantiations: output pixels per tile line (threads = 8 * TW)
 // and LDS pixels per column-chunk plane.  The plane size is 4 mod 16 so that
@@ -224,19 +224,33 @@ bool tile_geometry(const conv_plan *plan, int batch, int tw, int plane, TileGeom
     return true;
 }
 
-// Marching kernel: strips of kMarchTw output columns, a ring of kMarchNl input
-// lines in LDS, planes of kMarchLdsPixels / nv pixels per float4 column chunk.
-constexpr int kMarchTw = 64, kMarchNl = 16;
-constexpr int march_plane(int nv) { return nv == 4 ? 1156 : (nv == 2 ? 2308 : 4612); }   // 4 mod 16 each
+// Marching kernel: strips of tw output columns, a ring of kMarchNl input lines in
+// LDS.  Rows of up to 56 entries are shared by 8 lanes (strips of 64 columns),
+// rows of up to 128 entries by 16 lanes (strips of 32 columns); the workgroup
+// is 512 threads either way.
+constexpr int kMarchNl = 16, kMarchThreads = 512;
+constexpr int kMarchMinJobs = 256;           // fewer strip segments than this cannot fill the chip
+
+struct MarchShape { int g, nit, tw; };
+bool march_shape(int max_row_nnz, MarchShape *out) {
+    if (max_row_nnz <= 16) *out = MarchShape{8, 2, 64};
+    else if (max_row_nnz <= 32) *out = MarchShape{8, 4, 64};
+    else if (max_row_nnz <= 56) *out = MarchShape{8, 7, 64};
+    else if (max_row_nnz <= 96) *out = MarchShape{16, 6, 32};
+    else if (max_row_nnz <= 128) *out = MarchShape{16, 8, 32};
+    else return false;
+    return true;
+}
+constexpr int march_plane(int nv) { return nv == 4 ? 1156 : (nv == 2 ? 2308 : 4612); }   // 4 mod 16 each; nv 0 = one plane of floats
 constexpr int kMarchTargetBlocks = 512;      // two resident workgroups on each of 256 CUs
 
-bool march_geometry(const conv_plan *plan, int batch, int nv, MarchGeom *out, int *ls_out) {
+bool march_geometry(const conv_plan *plan, int batch, int nv, int tw, MarchGeom *out, int *ls_out) {
     const ConvShape &sh = plan->shape;
     MarchGeom g{};
     g.m = sh.m; g.n = sh.n; g.m_out = sh.m_out; g.n_out = sh.n_out; g.s = sh.s; g.p = sh.p; g.k = sh.k;
     g.batch = batch;
     g.nnz = (int)plan->nnz;
-    const int64_t iw = (int64_t)(kMarchTw - 1) * sh.s + sh.k;
+    const int64_t iw = (int64_t)(tw - 1) * sh.s + sh.k;
     const int plane = march_plane(nv);
     if (iw + 16 > plane) return false;
     g.iw = (int)iw;
@@ -244,17 +258,18 @@ bool march_geometry(const conv_plan *plan, int batch, int nv, MarchGeom *out, in
     if ((int64_t)kMarchNl * g.iw_pitch + 1 > plane) return false;
     // steps of two output lines when the ring and the per-thread line registers allow it
     // (LS = 2 is built with 2 float4 per thread, LS = 1 with 4), else one line per step
-    const int threads = kMarchTw * 8;
+    const int threads = kMarchThreads, planes = nv ? nv : 1;
     int ls = 0;
-    if ((int64_t)sh.s * 3 + sh.k <= kMarchNl && 2LL * sh.s * iw * nv <= 2LL * threads) ls = 2;
-    else if ((int64_t)sh.s + sh.k <= kMarchNl && (int64_t)sh.s * iw * nv <= 4LL * threads) ls = 1;
+    if ((int64_t)sh.s * 3 + sh.k <= kMarchNl && 2LL * sh.s * iw * planes <= 2LL * threads) ls = 2;
+    else if ((int64_t)sh.s + sh.k <= kMarchNl && (int64_t)sh.s * iw * planes <= 4LL * threads) ls = 1;
     if (ls == 0) return false;
     // int arithmetic in the kernel: s*x - p + k, col*16, d16 < 2^25 (see the kernel)
     if ((int64_t)sh.m + 2LL * sh.p + sh.k >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + iw >= (1LL << 30)) return false;
     if (plan->cols > (1LL << 27) || 2LL * kMarchNl * sh.n * 16 > (1LL << 25)) return false;
-    if (sh.n_out < kMarchTw / 2) return false;          // a strip would be mostly empty
-    g.strips = (sh.n_out + kMarchTw - 1) / kMarchTw;
-    const int col_blocks = batch / (4 * nv);
+    if (sh.n_out < tw / 2) return false;                // a strip would be mostly empty
+    g.strips = (sh.n_out + tw - 1) / tw;
+    const int col_blocks = nv ? batch / (4 * nv) : batch;
+    if ((int64_t)g.strips * ((sh.m_out + 7) / 8) * col_blocks < kMarchMinJobs) return false;
     int64_t segs = kMarchTargetBlocks / ((int64_t)g.strips * col_blocks);
     if (segs < 1) segs = 1;
     int64_t seg = (sh.m_out + segs - 1) / segs;
@@ -275,37 +290,36 @@ ApplyChoice choose_apply(const conv_plan *plan, const float *x, const float *y, 
     ApplyChoice c{};
     const bool aligned = ((((uintptr_t)x) | ((uintptr_t)y)) & 15u) == 0;
     c.g = group_width(plan->max_row_nnz);
-    if (!aligned || batch % 4 != 0) {
-        c.kind = Kind::GatherScalar;
-        c.nv = 0;
-        c.threads = kGatherThreads;
+    c.threads = kGatherThreads;
+    const bool vec = aligned && batch % 4 == 0;
+    c.nv = !vec ? 0 : (batch % 16 == 0 ? 4 : (batch % 8 == 0 ? 2 : 1));
+    c.kind = vec ? Kind::GatherVec : Kind::GatherScalar;
+    if (plan->nnz == 0 || (!vec && batch != 1) || (vec && batch / (4 * c.nv) > 65535)) return c;
+
+    // marching kernel: float4 column chunks, or one scalar column for a single vector (SpMV)
+    MarchShape ms;
+    MarchGeom mg;
+    int ls;
+    if (march_shape(plan->max_row_nnz, &ms) && march_geometry(plan, batch, c.nv, ms.tw, &mg, &ls)) {
+        c.kind = Kind::March;
+        c.g = ms.g;
+        c.nit = ms.nit;
+        c.tw = ms.tw;
+        c.threads = kMarchThreads;
+        c.lds = c.nv ? (size_t)c.nv * march_plane(c.nv) * 16 : (size_t)march_plane(0) * 4;
+        c.ls = ls;
+        c.march = mg;
         return c;
     }
-    c.nv = batch % 16 == 0 ? 4 : (batch % 8 == 0 ? 2 : 1);
-    c.kind = Kind::GatherVec;
-    c.threads = kGatherThreads;
-    // LDS-tiled kernel when the rows fit its unrolled trip count and the
+    if (!vec) return c;
+
+    // one LDS tile per workgroup when the rows fit its unrolled trip count and the
     // input window of at least one output line fits the LDS planes
     const int need = (plan->max_row_nnz + kTileG - 1) / kTileG;
     int nit = 0;
     for (int cand : kTileNit)
         if (cand >= need) { nit = cand; break; }
-    if (nit == 0 || batch / (4 * c.nv) > 65535 || plan->nnz == 0) return c;
-    {
-        MarchGeom mg;
-        int ls;
-        if (march_geometry(plan, batch, c.nv, &mg, &ls)) {
-            c.kind = Kind::March;
-            c.g = kTileG;
-            c.nit = nit;
-            c.tw = kMarchTw;
-            c.threads = kMarchTw * 8;
-            c.lds = (size_t)c.nv * march_plane(c.nv) * 16;
-            c.ls = ls;
-            c.march = mg;
-            return c;
-        }
-    }
+    if (nit == 0) return c;
     const int tws[2] = {kTileWide, kTileNarrow}, planes[2] = {kPlaneWide, kPlaneNarrow};
     for (int i = 0; i < 2; ++i) {
         TileGeom g;
@@ -376,9 +390,7 @@ bool launch_tile_nv(const ApplyChoice &c, const conv_plan *plan, const float *x,
     switch (c.nit) {
         case 2: return launch_tile_tw<2, NV>(c, plan, x, y, q);
         case 4: return launch_tile_tw<4, NV>(c, plan, x, y, q);
-        case 7: return launch_tile_tw<7, NV>(c, plan, x, y, q);
-        case 11: return launch_tile_tw<11, NV>(c, plan, x, y, q);
-        default: return launch_tile_tw<16, NV>(c, plan, x, y, q);
+        default: return launch_tile_tw<7, NV>(c, plan, x, y, q);
     }
 }
 
@@ -401,35 +413,38 @@ bool allow_large_lds(Kern kern, size_t lds, int dev, bool (&allowed)[64]) {
     return true;
 }
 
-template <int NIT, int NV, int LS, int XLD>
+template <int G, int NIT, int NV, int TW, int LS, int XLD>
 bool launch_march_inst(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
-    auto kern = spmm_march_kernel<kTileG, NIT, NV, kMarchTw, kMarchNl, LS, XLD, march_plane(NV)>;
+    auto kern = spmm_march_kernel<G, NIT, NV, TW, kMarchNl, LS, XLD, march_plane(NV)>;
     static thread_local bool allowed[64];
     if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
-    const dim3 grid((unsigned)(c.march.blocks_per_xcd * kXcds), (unsigned)(c.march.batch / (4 * NV)));
+    const dim3 grid((unsigned)(c.march.blocks_per_xcd * kXcds), (unsigned)(NV ? c.march.batch / (4 * NV) : c.march.batch));
     kern<<<grid, c.threads, c.lds, q>>>(plan->row_ptr, plan->col_idx, plan->vals, x, y, c.march);
     return true;
 }
 
-template <int NIT, int NV>
+template <int G, int NIT, int NV, int TW>
 bool launch_march_ls(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
-    if (c.ls == 2) return launch_march_inst<NIT, NV, 2, 2>(c, plan, x, y, q);
-    return launch_march_inst<NIT, NV, 1, 4>(c, plan, x, y, q);
+    if (c.ls == 2) return launch_march_inst<G, NIT, NV, TW, 2, 2>(c, plan, x, y, q);
+    return launch_march_inst<G, NIT, NV, TW, 1, 4>(c, plan, x, y, q);
 }
 
 template <int NV>
 bool launch_march_nv(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
-    switch (c.nit) {
-        case 2: return launch_march_ls<2, NV>(c, plan, x, y, q);
-        case 4: return launch_march_ls<4, NV>(c, plan, x, y, q);
-        case 7: return launch_march_ls<7, NV>(c, plan, x, y, q);
-        case 11: return launch_march_ls<11, NV>(c, plan, x, y, q);
-        default: return launch_march_ls<16, NV>(c, plan, x, y, q);
+    if (c.g == 8) {
+        switch (c.nit) {
+            case 2: return launch_march_ls<8, 2, NV, 64>(c, plan, x, y, q);
+            case 4: return launch_march_ls<8, 4, NV, 64>(c, plan, x, y, q);
+            default: return launch_march_ls<8, 7, NV, 64>(c, plan, x, y, q);
+        }
     }
+    if (c.nit == 6) return launch_march_ls<16, 6, NV, 32>(c, plan, x, y, q);
+    return launch_march_ls<16, 8, NV, 32>(c, plan, x, y, q);
 }
 
 bool launch_march(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
     switch (c.nv) {
+        case 0: return launch_march_nv<0>(c, plan, x, y, q);
         case 1: return launch_march_nv<1>(c, plan, x, y, q);
         case 2: return launch_march_nv<2>(c, plan, x, y, q);
         default: return launch_march_nv<4>(c, plan, x, y, q);
@@ -489,7 +504,10 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch) {
         case Kind::GatherScalar: snprintf(name, sizeof name, "gather_g%d_scalar", c.g); break;
         case Kind::GatherVec: snprintf(name, sizeof name, "gather_g%d_float4x%d", c.g, c.nv); break;
         case Kind::March:
-            snprintf(name, sizeof name, "lds_march_%dx%d_step%d_g%d_nit%d_float4x%d", c.march.seg, c.tw, c.ls, c.g, c.nit, c.nv);
+            if (c.nv)
+                snprintf(name, sizeof name, "lds_march_%dx%d_step%d_g%d_nit%d_float4x%d", c.march.seg, c.tw, c.ls, c.g, c.nit, c.nv);
+            else
+                snprintf(name, sizeof name, "lds_march_%dx%d_step%d_g%d_nit%d_scalar", c.march.seg, c.tw, c.ls, c.g, c.nit);
             break;
         case Kind::Tile:
             snprintf(name, sizeof name, "lds_tile_%dx%d_g%d_nit%d_float4x%d", c.geom.th, c.tw, c.g, c.nit, c.nv);
