@@ -108,6 +108,15 @@ const char *conv_strerror(int status);
  * library on the calling thread; 0 if none. */
 int conv_last_hip_error(void);
 
+/* Tuning knob of the apply dispatch (process-wide, thread-safe).  conv_spmv
+ * uses its persistent "marching" kernel only when the problem splits into at
+ * least `jobs` strip segments (64 or 32 output columns x 8 output lines x one
+ * block of batch columns); smaller problems cannot fill the chip that way and
+ * go to the row-group kernels.  Default 256.  Returns the previous value, or
+ * CONV_EINVAL for jobs < 1.  The result of conv_spmv does not depend on it
+ * beyond the summation order. */
+int conv_set_march_min_jobs(int jobs);
+
 #ifdef __cplusplus
 }
 #endif

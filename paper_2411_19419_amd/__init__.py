@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     conv_csr_build,
     conv_nnz,
     conv_out_shape,
+    conv_set_march_min_jobs,
     conv_spmv,
     conv_strerror,
     library_path,

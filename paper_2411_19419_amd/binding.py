@@ -19,6 +19,7 @@ _lib = None
 EXPORTS = (
     "conv_out_shape", "conv_nnz", "conv_csr_build", "conv_spmv", "conv_plan_shape",
     "conv_spmv_variant", "conv_plan_destroy", "conv_strerror", "conv_last_hip_error",
+    "conv_set_march_min_jobs",
 )
 
 
@@ -63,12 +64,22 @@ def _load():
         lib.conv_strerror.restype = ctypes.c_char_p
         lib.conv_last_hip_error.argtypes = []
         lib.conv_last_hip_error.restype = i
+        lib.conv_set_march_min_jobs.argtypes = [i]
+        lib.conv_set_march_min_jobs.restype = i
         _lib = lib
         return lib
 
 
 def conv_strerror(status: int) -> str:
     return _load().conv_strerror(int(status)).decode()
+
+
+def conv_set_march_min_jobs(jobs: int) -> int:
+    """Set the dispatch knob; returns the previous value."""
+    prev = _load().conv_set_march_min_jobs(int(jobs))
+    if prev < 0:
+        raise ConvError(prev, "conv_set_march_min_jobs(%r)" % (jobs,))
+    return prev
 
 
 def conv_out_shape(m, n, k, s, p):

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdio>
 #include <new>
 
@@ -163,6 +164,7 @@ struct ApplyChoice {
     size_t lds;
     TileGeom geom;
     int ls;         // march kernel: output lines per step
+    int nl;         // march kernel: ring lines
     MarchGeom march;
 };
 
@@ -224,12 +226,14 @@ bool tile_geometry(const conv_plan *plan, int batch, int tw, int plane, TileGeom
     return true;
 }
 
-// Marching kernel: strips of tw output columns, a ring of kMarchNl input lines in
+// Marching kernel: strips of tw output columns, a ring of 16 or 8 input lines in
 // LDS.  Rows of up to 56 entries are shared by 8 lanes (strips of 64 columns),
 // rows of up to 128 entries by 16 lanes (strips of 32 columns); the workgroup
 // is 512 threads either way.
-constexpr int kMarchNl = 16, kMarchThreads = 512;
-constexpr int kMarchMinJobs = 256;           // fewer strip segments than this cannot fill the chip
+constexpr int kMarchThreads = 512;
+// Fewer strip segments than this cannot fill the chip; the row-group kernels
+// take such problems.  Adjustable through conv_set_march_min_jobs.
+std::atomic<int> g_march_min_jobs{256};
 
 struct MarchShape { int g, nit, tw; };
 bool march_shape(int max_row_nnz, MarchShape *out) {
@@ -244,7 +248,7 @@ bool march_shape(int max_row_nnz, MarchShape *out) {
 constexpr int march_plane(int nv) { return nv == 4 ? 1156 : (nv == 2 ? 2308 : 4612); }   // 4 mod 16 each; nv 0 = one plane of floats
 constexpr int kMarchTargetBlocks = 512;      // two resident workgroups on each of 256 CUs
 
-bool march_geometry(const conv_plan *plan, int batch, int nv, int tw, MarchGeom *out, int *ls_out) {
+bool march_geometry(const conv_plan *plan, int batch, int nv, int tw, MarchGeom *out, int *ls_out, int *nl_out) {
     const ConvShape &sh = plan->shape;
     MarchGeom g{};
     g.m = sh.m; g.n = sh.n; g.m_out = sh.m_out; g.n_out = sh.n_out; g.s = sh.s; g.p = sh.p; g.k = sh.k;
@@ -255,21 +259,24 @@ bool march_geometry(const conv_plan *plan, int batch, int nv, int tw, MarchGeom 
     if (iw + 16 > plane) return false;
     g.iw = (int)iw;
     g.iw_pitch = round_up_mod((int)iw, 16, 8);
-    if ((int64_t)kMarchNl * g.iw_pitch + 1 > plane) return false;
-    // steps of two output lines when the ring and the per-thread line registers allow it
-    // (LS = 2 is built with 2 float4 per thread, LS = 1 with 4), else one line per step
+    // Ring of 16 lines with steps of two output lines when the ring (s*3 + k lines in
+    // use or arriving), the LDS plane and the per-thread line registers (2 per thread)
+    // allow it; else steps of one line (s + k lines, 4 registers) with 16 or 8 ring lines.
     const int threads = kMarchThreads, planes = nv ? nv : 1;
-    int ls = 0;
-    if ((int64_t)sh.s * 3 + sh.k <= kMarchNl && 2LL * sh.s * iw * planes <= 2LL * threads) ls = 2;
-    else if ((int64_t)sh.s + sh.k <= kMarchNl && (int64_t)sh.s * iw * planes <= 4LL * threads) ls = 1;
+    const bool regs1 = (int64_t)sh.s * iw * planes <= 4LL * threads;
+    auto fits = [&](int nl) { return (int64_t)nl * g.iw_pitch + 1 <= plane; };
+    int ls = 0, nl = 0;
+    if ((int64_t)sh.s * 3 + sh.k <= 16 && 2LL * sh.s * iw * planes <= 2LL * threads && fits(16)) { ls = 2; nl = 16; }
+    else if ((int64_t)sh.s + sh.k <= 16 && regs1 && fits(16)) { ls = 1; nl = 16; }
+    else if ((int64_t)sh.s + sh.k <= 8 && regs1 && fits(8)) { ls = 1; nl = 8; }
     if (ls == 0) return false;
     // int arithmetic in the kernel: s*x - p + k, col*16, d16 < 2^25 (see the kernel)
     if ((int64_t)sh.m + 2LL * sh.p + sh.k >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + iw >= (1LL << 30)) return false;
-    if (plan->cols > (1LL << 27) || 2LL * kMarchNl * sh.n * 16 > (1LL << 25)) return false;
+    if (plan->cols > (1LL << 27) || 2LL * 16 * sh.n * 16 > (1LL << 25)) return false;
     if (sh.n_out < tw / 2) return false;                // a strip would be mostly empty
     g.strips = (sh.n_out + tw - 1) / tw;
     const int col_blocks = nv ? batch / (4 * nv) : batch;
-    if ((int64_t)g.strips * ((sh.m_out + 7) / 8) * col_blocks < kMarchMinJobs) return false;
+    if ((int64_t)g.strips * ((sh.m_out + 7) / 8) * col_blocks < g_march_min_jobs.load(std::memory_order_relaxed)) return false;
     int64_t segs = kMarchTargetBlocks / ((int64_t)g.strips * col_blocks);
     if (segs < 1) segs = 1;
     int64_t seg = (sh.m_out + segs - 1) / segs;
@@ -283,6 +290,7 @@ bool march_geometry(const conv_plan *plan, int batch, int nv, int tw, MarchGeom 
     g.inv_n = 1.0f / (float)sh.n;
     *out = g;
     *ls_out = ls;
+    *nl_out = nl;
     return true;
 }
 
@@ -299,8 +307,8 @@ ApplyChoice choose_apply(const conv_plan *plan, const float *x, const float *y, 
     // marching kernel: float4 column chunks, or one scalar column for a single vector (SpMV)
     MarchShape ms;
     MarchGeom mg;
-    int ls;
-    if (march_shape(plan->max_row_nnz, &ms) && march_geometry(plan, batch, c.nv, ms.tw, &mg, &ls)) {
+    int ls, nl;
+    if (march_shape(plan->max_row_nnz, &ms) && march_geometry(plan, batch, c.nv, ms.tw, &mg, &ls, &nl)) {
         c.kind = Kind::March;
         c.g = ms.g;
         c.nit = ms.nit;
@@ -308,6 +316,7 @@ ApplyChoice choose_apply(const conv_plan *plan, const float *x, const float *y, 
         c.threads = kMarchThreads;
         c.lds = c.nv ? (size_t)c.nv * march_plane(c.nv) * 16 : (size_t)march_plane(0) * 4;
         c.ls = ls;
+        c.nl = nl;
         c.march = mg;
         return c;
     }
@@ -413,9 +422,9 @@ bool allow_large_lds(Kern kern, size_t lds, int dev, bool (&allowed)[64]) {
     return true;
 }
 
-template <int G, int NIT, int NV, int TW, int LS, int XLD>
+template <int G, int NIT, int NV, int TW, int NL, int LS, int XLD>
 bool launch_march_inst(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
-    auto kern = spmm_march_kernel<G, NIT, NV, TW, kMarchNl, LS, XLD, march_plane(NV)>;
+    auto kern = spmm_march_kernel<G, NIT, NV, TW, NL, LS, XLD, march_plane(NV)>;
     static thread_local bool allowed[64];
     if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
     const dim3 grid((unsigned)(c.march.blocks_per_xcd * kXcds), (unsigned)(NV ? c.march.batch / (4 * NV) : c.march.batch));
@@ -425,8 +434,9 @@ bool launch_march_inst(const ApplyChoice &c, const conv_plan *plan, const float 
 
 template <int G, int NIT, int NV, int TW>
 bool launch_march_ls(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
-    if (c.ls == 2) return launch_march_inst<G, NIT, NV, TW, 2, 2>(c, plan, x, y, q);
-    return launch_march_inst<G, NIT, NV, TW, 1, 4>(c, plan, x, y, q);
+    if (c.ls == 2) return launch_march_inst<G, NIT, NV, TW, 16, 2, 2>(c, plan, x, y, q);
+    if (c.nl == 16) return launch_march_inst<G, NIT, NV, TW, 16, 1, 4>(c, plan, x, y, q);
+    return launch_march_inst<G, NIT, NV, TW, 8, 1, 4>(c, plan, x, y, q);
 }
 
 template <int NV>
@@ -505,9 +515,9 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch) {
         case Kind::GatherVec: snprintf(name, sizeof name, "gather_g%d_float4x%d", c.g, c.nv); break;
         case Kind::March:
             if (c.nv)
-                snprintf(name, sizeof name, "lds_march_%dx%d_step%d_g%d_nit%d_float4x%d", c.march.seg, c.tw, c.ls, c.g, c.nit, c.nv);
+                snprintf(name, sizeof name, "lds_march_%dx%d_ring%d_step%d_g%d_nit%d_float4x%d", c.march.seg, c.tw, c.nl, c.ls, c.g, c.nit, c.nv);
             else
-                snprintf(name, sizeof name, "lds_march_%dx%d_step%d_g%d_nit%d_scalar", c.march.seg, c.tw, c.ls, c.g, c.nit);
+                snprintf(name, sizeof name, "lds_march_%dx%d_ring%d_step%d_g%d_nit%d_scalar", c.march.seg, c.tw, c.nl, c.ls, c.g, c.nit);
             break;
         case Kind::Tile:
             snprintf(name, sizeof name, "lds_tile_%dx%d_g%d_nit%d_float4x%d", c.geom.th, c.tw, c.g, c.nit, c.nv);
@@ -544,5 +554,10 @@ const char *conv_strerror(int status) {
 }
 
 int conv_last_hip_error(void) { return g_last_hip_error; }
+
+int conv_set_march_min_jobs(int jobs) {
+    if (jobs < 1) return CONV_EINVAL;
+    return g_march_min_jobs.exchange(jobs);
+}
 
 }  // extern "C"

@@ -184,3 +184,141 @@ def test_errors_on_device_calls():
     assert lib.conv_spmv(plan._handle, buf.data_ptr(), buf.data_ptr() + 400, 0, None) == -1      # batch < 1
     assert lib.conv_spmv(plan._handle, None, buf.data_ptr(), 1, None) == -2
     plan.close()
+
+
+# ---------------------------------------------------------------------------
+# The same checks with the dispatch knob set so that the persistent marching
+# kernel is used wherever its geometry allows, however small the shape: partial
+# strips, short segments, steps that run off the image, rows of every length.
+# ---------------------------------------------------------------------------
+
+@pytest.fixture
+def march_everywhere():
+    prev = cs.conv_set_march_min_jobs(1)
+    yield
+    cs.conv_set_march_min_jobs(prev)
+
+
+def test_march_exhaustive_tiny_grid(march_everywhere):
+    batches = itertools.cycle([1, 4, 8, 16])
+    count = used = 0
+    for shape in itertools.product(range(1, 6), range(1, 6), range(1, 5), range(1, 4), range(0, 5)):
+        m, n, k, s, p = shape
+        if k > m + 2 * p or k > n + 2 * p:
+            continue
+        batch = next(batches)
+        x, K = _rand(shape, batch, 1000 + count)
+        plan = build_plan(shape, K)
+        used += plan.variant(batch).startswith("lds_march")
+        check_apply(plan, shape, K, x, batch)
+        plan.close()
+        count += 1
+    assert count > 1000
+
+
+MARCH_CASES = [
+    ((37, 53, 7, 1, 3), 16), ((130, 67, 7, 1, 3), 16), ((64, 64, 7, 1, 3), 16), ((65, 129, 7, 1, 3), 1),
+    ((100, 90, 5, 2, 2), 16), ((100, 90, 5, 2, 2), 8), ((100, 90, 5, 2, 2), 4), ((100, 90, 5, 2, 2), 1),
+    ((33, 200, 3, 1, 1), 32), ((33, 200, 3, 1, 1), 1), ((70, 70, 1, 1, 0), 16), ((70, 70, 2, 2, 0), 8),
+    ((75, 75, 9, 3, 8), 4), ((75, 75, 9, 3, 8), 16), ((75, 75, 9, 3, 8), 1), ((75, 75, 9, 3, 8), 8),
+    ((90, 141, 11, 4, 5), 4), ((90, 141, 11, 4, 5), 1), ((150, 150, 11, 1, 5), 8), ((150, 150, 11, 1, 5), 16),
+    ((140, 40, 7, 3, 3), 16), ((40, 140, 7, 5, 0), 4), ((200, 200, 3, 2, 1), 16), ((120, 120, 9, 1, 4), 16),
+    ((3, 150, 7, 2, 3), 4), ((50, 50, 2, 1, 5), 8), ((64, 64, 4, 1, 6), 1), ((97, 33, 6, 1, 2), 12),
+]
+
+
+def test_march_ragged_shapes(march_everywhere):
+    """Ring of 16 and of 8 lines, steps of one and two lines, 8 and 16 lanes per
+    row, scalar / float4 x 1, 2, 4 columns.  A few of the cases do not fit the LDS
+    planes and fall back; most must take the marching kernel."""
+    variants = {}
+    for shape, batch in MARCH_CASES:
+        x, K = _rand(shape, batch, 17)
+        plan = build_plan(shape, K)
+        variants[(shape, batch)] = plan.variant(batch)
+        check_apply(plan, shape, K, x, batch)
+        plan.close()
+    marching = [v for v in variants.values() if v.startswith("lds_march")]
+    print(variants)
+    assert len(marching) >= 22, variants
+    kinds = {v.split("_", 3)[3] for v in marching}          # ring/step/lanes/trip/columns
+    assert len(kinds) >= 10, kinds
+
+
+@pytest.mark.parametrize("shape", sorted(set(workloads.densenet121_layer_shapes())))
+@pytest.mark.parametrize("batch", [1, 4, 16])
+def test_march_densenet_layer_shapes(march_everywhere, shape, batch):
+    x, K = _rand(shape, batch, 300 + batch)
+    plan = build_plan(shape, K)
+    check_apply(plan, shape, K, x, batch)
+    plan.close()
+
+
+@pytest.mark.parametrize("batch", [1, 16])
+def test_march_reads_the_stored_arrays(march_everywhere, batch):
+    """Edited arrays under the marching kernel: a column far outside the resident
+    lines must be fetched from global memory (the cold path), scaled values scale y."""
+    shape = (96, 80, 7, 1, 3)
+    m, n, k, s, p = shape
+    x, K = _rand(shape, batch, 23)
+    plan = build_plan(shape, K)
+    assert plan.variant(batch).startswith("lds_march")
+    xd = torch.from_numpy(x).to(device())
+    y0 = cs.conv_spmv(plan, xd, batch=batch).clone()
+    plan.vals.mul_(2.0)
+    y1 = cs.conv_spmv(plan, xd, batch=batch).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(y1, 2.0 * y0)
+    plan.vals.mul_(0.5)
+    rp, ci, va = oracle.csr(m, n, k, s, p, K)
+    edits = {40 * plan.n_out + 9: ((m - 1) * n + (n - 1), 3),      # far below the window
+             41 * plan.n_out + 70: (0, 0),                          # far above it
+             7 * plan.n_out + 33: (7 * n + 79, 10)}                 # right line, column outside the strip
+    ci2 = ci.copy()
+    for row, (new_col, slot) in edits.items():
+        e = int(rp[row]) + slot
+        plan.col_idx[e] = new_col
+        ci2[e] = new_col
+    y2 = cs.conv_spmv(plan, xd, batch=batch)
+    torch.cuda.synchronize()
+    y0h, y2h = y0.cpu().numpy().reshape(-1, batch), y2.cpu().numpy().reshape(-1, batch)
+    X = x.reshape(-1, batch).astype(np.float64)
+    changed = np.where(np.any(y0h != y2h, axis=1))[0]
+    assert sorted(changed.tolist()) == sorted(edits)
+    for row in edits:
+        seg = slice(int(rp[row]), int(rp[row + 1]))
+        want = (va[seg].astype(np.float64)[:, None] * X[ci2[seg]]).sum(axis=0)
+        scale = (np.abs(va[seg]).astype(np.float64)[:, None] * np.abs(X[ci2[seg]])).sum(axis=0)
+        assert np.all(np.abs(y2h[row] - want) <= 1e-5 * scale)
+    plan.close()
+
+
+def test_march_is_repeatable_bit_for_bit(march_everywhere):
+    shape, batch = (130, 70, 5, 1, 2), 16
+    x, K = _rand(shape, batch, 29)
+    plan = build_plan(shape, K)
+    xd = torch.from_numpy(x).to(device())
+    ys = [cs.conv_spmv(plan, xd, batch=batch).clone() for _ in range(3)]
+    torch.cuda.synchronize()
+    assert torch.equal(ys[0], ys[1]) and torch.equal(ys[0], ys[2])
+    plan.close()
+
+
+def test_inf_and_nan_stay_in_their_rows(march_everywhere):
+    """A non-finite input pixel must reach exactly the outputs whose windows contain it."""
+    shape, batch = (70, 70, 3, 1, 1), 4
+    m, n, k, s, p = shape
+    x, K = _rand(shape, batch, 31)
+    K = np.abs(K) + 0.5
+    x = x.copy()
+    bad = (30 * n + 40) * batch + 2
+    x[bad] = np.inf
+    plan = build_plan(shape, K)
+    y = cs.conv_spmv(plan, torch.from_numpy(x).to(device()), batch=batch)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy().reshape(plan.m_out, plan.n_out, batch)
+    nonfinite = ~np.isfinite(got)
+    want = np.zeros_like(nonfinite)
+    want[29:32, 39:42, 2] = True
+    assert np.array_equal(nonfinite, want)
+    plan.close()
