@@ -104,8 +104,7 @@ int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, i
     if (nnz > kInt32Limit || cols > kInt32Limit || rows >= kInt32Limit || (int64_t)k * k > kInt32Limit ||
         mo * (int64_t)k > kInt32Limit || no * (int64_t)k > kInt32Limit)
         return CONV_EOVERFLOW;
-    constexpr int G = 8;
-    const int64_t fill_blocks = mo * ((no + kFillThreads / G - 1) / (kFillThreads / G));
+    const int64_t fill_blocks = mo * ((no + kFillRows - 1) / kFillRows);
     const int64_t rp_blocks = mo * ((no + kRowPtrThreads - 1) / kRowPtrThreads);
     if (fill_blocks > kInt32Limit || rp_blocks > kInt32Limit) return CONV_EOVERFLOW;
     if (!row_ptr_dev || !kernel_dev || (nnz > 0 && (!col_idx_dev || !vals_dev))) return CONV_ENULL;
@@ -134,7 +133,7 @@ int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, i
     axis_prefix_kernel<<<2, kAxisThreads, 0, q>>>(plan->shape, plan->axis_tab);
     row_ptr_kernel<<<(unsigned)rp_blocks, kRowPtrThreads, 0, q>>>(plan->shape, plan->axis_tab, row_ptr_dev);
     if (nnz > 0)
-        csr_fill_kernel<G><<<(unsigned)fill_blocks, kFillThreads, 0, q>>>(plan->shape, plan->axis_tab, kernel_dev,
+        csr_fill_kernel<<<(unsigned)fill_blocks, kFillThreads, 0, q>>>(plan->shape, plan->axis_tab, kernel_dev,
                                                                          col_idx_dev, vals_dev);
     if (!hip_ok(hipGetLastError())) {
         (void)hipFree(plan->axis_tab);
