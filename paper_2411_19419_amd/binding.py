@@ -186,9 +186,13 @@ def conv_spmv(plan: ConvPlan, x, y=None, batch: int = 1, stream=None):
     elif not (y.is_cuda and y.dtype == torch.float32 and y.is_contiguous()
               and y.numel() == plan.rows * batch):
         raise ValueError("y must be a contiguous float32 device tensor with m_out*n_out*batch elements")
-    with torch.cuda.device(x.device):
+    if x.device.index == torch.cuda.current_device():        # the usual case: no device switch
         sh, _ = _stream_handle(stream)
         st = _load().conv_spmv(plan._handle, x.data_ptr(), y.data_ptr(), int(batch), sh)
+    else:
+        with torch.cuda.device(x.device):
+            sh, _ = _stream_handle(stream)
+            st = _load().conv_spmv(plan._handle, x.data_ptr(), y.data_ptr(), int(batch), sh)
     if st != 0:
         raise ConvError(st, "conv_spmv(batch=%d)" % batch)
     return y

@@ -260,9 +260,9 @@ bool march_geometry(const conv_plan *plan, int batch, int nv, int tw, MarchGeom 
     g.iw_pitch = round_up_mod((int)iw, 16, 8);
     // Ring of 16 lines with steps of two output lines when the ring (s*3 + k lines in
     // use or arriving), the LDS plane and the per-thread line registers (2 per thread)
-    // allow it; else steps of one line (s + k lines, 4 registers) with 16 or 8 ring lines.
+    // allow it; else steps of one line (s + k lines, 2 registers) with 16 or 8 ring lines.
     const int threads = kMarchThreads, planes = nv ? nv : 1;
-    const bool regs1 = (int64_t)sh.s * iw * planes <= 4LL * threads;
+    const bool regs1 = (int64_t)sh.s * iw * planes <= 2LL * threads;
     auto fits = [&](int nl) { return (int64_t)nl * g.iw_pitch + 1 <= plane; };
     int ls = 0, nl = 0;
     if ((int64_t)sh.s * 3 + sh.k <= 16 && 2LL * sh.s * iw * planes <= 2LL * threads && fits(16)) { ls = 2; nl = 16; }
@@ -434,8 +434,8 @@ bool launch_march_inst(const ApplyChoice &c, const conv_plan *plan, const float 
 template <int G, int NIT, int NV, int TW>
 bool launch_march_ls(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
     if (c.ls == 2) return launch_march_inst<G, NIT, NV, TW, 16, 2, 2>(c, plan, x, y, q);
-    if (c.nl == 16) return launch_march_inst<G, NIT, NV, TW, 16, 1, 4>(c, plan, x, y, q);
-    return launch_march_inst<G, NIT, NV, TW, 8, 1, 4>(c, plan, x, y, q);
+    if (c.nl == 16) return launch_march_inst<G, NIT, NV, TW, 16, 1, 2>(c, plan, x, y, q);
+    return launch_march_inst<G, NIT, NV, TW, 8, 1, 2>(c, plan, x, y, q);
 }
 
 template <int NV>
