@@ -74,6 +74,15 @@ int conv_csr_build(int m, int n, int k, int s, int p,
                    int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev,
                    void *stream, conv_plan **plan_out);
 
+/* Replace the kernel of a built T: rewrites the plan's vals array from a new
+ * K of the same size (k*k fp32, row-major, device); row_ptr and col_idx do not
+ * depend on K and are left alone.  The paper notes (Section 4.2) that the
+ * method is at a disadvantage when the kernel changes, because the
+ * transformation has to be recomputed; this call is that recomputation
+ * reduced to one pass over vals.  Enqueues on `stream`; must not overlap an
+ * apply of the same plan. */
+int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream);
+
 /* Apply: y = T x (Section 3, the convolution procedure: vec, multiply,
  * un-vec; vec and its inverse are reinterpretations and move nothing).
  *   x_dev : m*n*batch fp32, batch-minor, device, read.
@@ -107,6 +116,23 @@ const char *conv_strerror(int status);
 /* hipError_t (as int) of the most recent failing HIP call made by this
  * library on the calling thread; 0 if none. */
 int conv_last_hip_error(void);
+
+/* Many small products in one launch.  The paper's experiment (Section 4.1,
+ * Table 2) applies 123 small independent transformations, each far cheaper
+ * than a kernel launch; conv_multi_create binds n plans to their operands
+ *   x_dev[i] : cols_i*batch fp32, batch-minor, device, read by every apply,
+ *   y_dev[i] : rows_i*batch fp32, batch-minor, device, written by every apply,
+ * (the same batch for all) and conv_multi_apply computes y_i = T_i x_i for all
+ * i with a single kernel launch on `stream`.  The plans, their CSR arrays and
+ * the operand buffers are borrowed and must outlive the object; the object
+ * owns a device array of n descriptors (hipMalloc and a blocking copy in
+ * create).  All plans must live on the same device; x_i and y_i must not
+ * overlap.  Results are those of conv_spmv up to summation order. */
+typedef struct conv_multi conv_multi;
+int conv_multi_create(int n, const conv_plan *const *plans, const float *const *x_dev,
+                      float *const *y_dev, int batch, conv_multi **multi_out);
+int conv_multi_apply(const conv_multi *multi, void *stream);
+int conv_multi_destroy(conv_multi *multi);   /* NULL is accepted */
 
 /* Tuning knob of the apply dispatch (process-wide, thread-safe).  conv_spmv
  * uses its persistent "marching" kernel only when the problem splits into at

@@ -6,6 +6,7 @@ The compute lives in ``libconvspmv.so`` (C ABI declared in
 """
 from .binding import (  # noqa: F401
     ConvError,
+    ConvMulti,
     ConvPlan,
     conv_csr_build,
     conv_nnz,
@@ -13,5 +14,6 @@ from .binding import (  # noqa: F401
     conv_set_march_min_jobs,
     conv_spmv,
     conv_strerror,
+    conv_update_kernel,
     library_path,
 )

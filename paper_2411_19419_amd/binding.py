@@ -19,7 +19,8 @@ _lib = None
 EXPORTS = (
     "conv_out_shape", "conv_nnz", "conv_csr_build", "conv_spmv", "conv_plan_shape",
     "conv_spmv_variant", "conv_plan_destroy", "conv_strerror", "conv_last_hip_error",
-    "conv_set_march_min_jobs",
+    "conv_set_march_min_jobs", "conv_update_kernel",
+    "conv_multi_create", "conv_multi_apply", "conv_multi_destroy",
 )
 
 
@@ -64,6 +65,15 @@ def _load():
         lib.conv_strerror.restype = ctypes.c_char_p
         lib.conv_last_hip_error.argtypes = []
         lib.conv_last_hip_error.restype = i
+        lib.conv_multi_create.argtypes = [i, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), i,
+                                          ctypes.POINTER(vp)]
+        lib.conv_multi_create.restype = i
+        lib.conv_multi_apply.argtypes = [vp, vp]
+        lib.conv_multi_apply.restype = i
+        lib.conv_multi_destroy.argtypes = [vp]
+        lib.conv_multi_destroy.restype = i
+        lib.conv_update_kernel.argtypes = [vp, vp, vp]
+        lib.conv_update_kernel.restype = i
         lib.conv_set_march_min_jobs.argtypes = [i]
         lib.conv_set_march_min_jobs.restype = i
         _lib = lib
@@ -172,6 +182,22 @@ def conv_csr_build(m, n, k, s, p, kernel, stream=None) -> ConvPlan:
     return ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, row_ptr, col_idx, vals, kernel)
 
 
+def conv_update_kernel(plan: ConvPlan, kernel, stream=None) -> None:
+    """Rewrite plan.vals for a new k*k kernel (device tensor); indices are untouched."""
+    import torch
+    if plan._handle is None:
+        raise ValueError("plan is closed")
+    if not (kernel.is_cuda and kernel.dtype == torch.float32 and kernel.is_contiguous()
+            and kernel.numel() == plan.k * plan.k):
+        raise ValueError("kernel must be a contiguous float32 device tensor with k*k elements")
+    with torch.cuda.device(kernel.device):
+        sh, _ = _stream_handle(stream)
+        st = _load().conv_update_kernel(plan._handle, kernel.data_ptr(), sh)
+    if st != 0:
+        raise ConvError(st, "conv_update_kernel")
+    plan._kernel = kernel
+
+
 def conv_spmv(plan: ConvPlan, x, y=None, batch: int = 1, stream=None):
     """y = T x for `batch` batch-minor vectors.  Allocates y when not given."""
     import torch
@@ -196,3 +222,50 @@ def conv_spmv(plan: ConvPlan, x, y=None, batch: int = 1, stream=None):
     if st != 0:
         raise ConvError(st, "conv_spmv(batch=%d)" % batch)
     return y
+
+
+class ConvMulti:
+    """n plans bound to their operands; apply() is one kernel launch for all of them."""
+
+    def __init__(self, plans, xs, ys, batch: int = 1):
+        import torch
+        n = len(plans)
+        if not (n == len(xs) == len(ys)) or n == 0:
+            raise ValueError("plans, xs and ys must be non-empty and of equal length")
+        for pl, x, y in zip(plans, xs, ys):
+            if pl._handle is None:
+                raise ValueError("a plan is closed")
+            for t, size in ((x, pl.cols * batch), (y, pl.rows * batch)):
+                if not (t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() == size):
+                    raise ValueError("operands must be contiguous float32 device tensors of the plan's size")
+        arr = ctypes.c_void_p * n
+        handle = ctypes.c_void_p()
+        with torch.cuda.device(xs[0].device):
+            st = _load().conv_multi_create(n, arr(*[pl._handle for pl in plans]), arr(*[x.data_ptr() for x in xs]),
+                                           arr(*[y.data_ptr() for y in ys]), int(batch), ctypes.byref(handle))
+        if st != 0:
+            raise ConvError(st, "conv_multi_create")
+        self._handle = handle
+        self._keep = (list(plans), list(xs), list(ys))     # borrowed by the library
+        self.ys = list(ys)
+        self.batch = batch
+
+    def apply(self, stream=None):
+        sh, _ = _stream_handle(stream)
+        st = _load().conv_multi_apply(self._handle, sh)
+        if st != 0:
+            raise ConvError(st, "conv_multi_apply")
+        return self.ys
+
+    def close(self):
+        if self._handle is not None:
+            import torch
+            torch.cuda.synchronize()
+            _load().conv_multi_destroy(self._handle)
+            self._handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

@@ -84,4 +84,55 @@ __global__ __launch_bounds__(kGatherThreads) void spmm_gather_vec_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------
+// Many small products in one launch.  The paper's experiment (Section 4.1)
+// applies 123 small, independent transformations (the DenseNet121 layer shapes
+// of Table 2, 7x7 ... 224x224 pixels); each of them is a few microseconds of
+// work, far less than a kernel launch costs.  Here every product i has a
+// descriptor, the grid is the concatenation of the products' row blocks, and a
+// workgroup finds its product by bisection over first_block.  Inside a
+// product the row-group scheme of the gather kernels is used with a per-product
+// group width (1 << g_shift lanes per row).
+// ---------------------------------------------------------------------------
+struct MultiDesc {
+    const int *row_ptr;
+    const int *col_idx;
+    const float *vals;
+    const float *x;
+    float *y;
+    int rows;
+    int g_shift;          // log2 of the lanes per row, 0..4
+    int first_block;      // first workgroup of this product in the launch
+    int pad;
+};
+
+__global__ __launch_bounds__(kGatherThreads) void spmm_multi_kernel(const MultiDesc *__restrict__ descs, int n,
+                                                                    int batch) {
+    int lo = 0, hi = n;                  // descs[lo].first_block <= blockIdx.x < descs[hi].first_block
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (descs[mid].first_block <= (int)blockIdx.x) lo = mid; else hi = mid;
+    }
+    const MultiDesc d = descs[lo];
+    const int gs = d.g_shift, G = 1 << gs;
+    const long long row = ((long long)(blockIdx.x - d.first_block) * kGatherThreads + threadIdx.x) >> gs;
+    const int lane = (int)threadIdx.x & (G - 1);
+    int beg = 0, end = 0;
+    if (row < d.rows) {
+        beg = d.row_ptr[row];
+        end = d.row_ptr[row + 1];
+    }
+    for (int c = blockIdx.y; c < batch; c += gridDim.y) {   // uniform over the block
+        float acc = 0.0f;
+        for (int e = beg + lane; e < end; e += G)
+            acc = fmaf(d.vals[e], d.x[(long long)d.col_idx[e] * batch + c], acc);
+        // butterfly over the group; gs is uniform over the block, all lanes are active
+        if (gs >= 1) acc += dpp_move<kDppXor1>(acc);
+        if (gs >= 2) acc += dpp_move<kDppXor2>(acc);
+        if (gs >= 3) acc += dpp_move<kDppXor7>(acc);
+        if (gs >= 4) acc += dpp_move<kDppXor15>(acc);
+        if (row < d.rows && lane == 0) d.y[row * batch + c] = acc;
+    }
+}
+
 }  // namespace convspmv

@@ -98,20 +98,6 @@ __global__ __launch_bounds__(512, 4) void spmm_march_kernel(const int *__restric
     auto line_lo = [&](int xo) { return min(max(g.s * xo - g.p, 0), g.m); };
     auto line_hi = [&](int xo, int cnt) { return min(max(g.s * (xo + cnt - 1) - g.p + g.k, 0), g.m); };
 
-    {   // lines of the first step -> LDS
-        const int lo = line_lo(xa), hi = line_hi(xa, LS);
-        const int items = (hi - lo) * iwc * NP;
-        for (int item = tid; item < items; item += NTHREADS) {
-            const int q = item / NP, v = item % NP;
-            const int dl = div_small(q, inv_iwc), dj = q - dl * iwc;
-            const int i = lo + dl;
-            const elem_t *src = reinterpret_cast<const elem_t *>(x + ((long long)i * g.n + (j0 + dj)) * g.batch + c0);
-            xs[v * CS + (i & (NL - 1)) * g.iw_pitch + dj] = src[v];
-        }
-        if (tid < NP) xs[tid * CS + zslot] = elem_t(0.0f);
-    }
-    __syncthreads();
-
     // ---- per-lane row of T on output line xo: bounds, clamped so that every lane holds
     // valid, ascending entry indices (a lane without a row gets an empty range)
     struct Bounds { int beg, end; };
@@ -297,9 +283,25 @@ __global__ __launch_bounds__(512, 4) void spmm_march_kernel(const int *__restric
     // ---- the march.  Output line xa + i is pass i of every wave; passes come in pairs
     // (two entry register sets), LS passes form a step.
     const int npass = (xb - xa + 1) & ~1;
+    // The first bounds and entries are requested before the first input lines, so that the
+    // two round trips of the entry stream (row_ptr, then entries) overlap the window load.
     Bounds b_next = load_bounds(xa), b_next2 = load_bounds(xa + 1);
     Pass pa, pb;
     fetch(b_next, pa);
+    {   // lines of the first step -> LDS
+        const int lo = line_lo(xa), hi = line_hi(xa, LS);
+        const int items = (hi - lo) * iwc * NP;
+        for (int item = tid; item < items; item += NTHREADS) {
+            const int q = item / NP, v = item % NP;
+            const int dl = div_small(q, inv_iwc), dj = q - dl * iwc;
+            const int i = lo + dl;
+            const elem_t *src = reinterpret_cast<const elem_t *>(x + ((long long)i * g.n + (j0 + dj)) * g.batch + c0);
+            xs[v * CS + (i & (NL - 1)) * g.iw_pitch + dj] = src[v];
+        }
+        if (tid < NP) xs[tid * CS + zslot] = elem_t(0.0f);
+    }
+    __syncthreads();
+
     for (int i = 0; i < npass; i += 2) {
         const int xo = xa + i;
         // -- pass i (entries in pa)

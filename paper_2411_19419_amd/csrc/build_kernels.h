@@ -100,6 +100,9 @@ __global__ __launch_bounds__(kRowPtrThreads) void row_ptr_kernel(ConvShape sh, c
 constexpr int kFillThreads = 256;
 constexpr int kFillRows = 256;
 
+// COLS = false rewrites vals only (a new kernel for the same shape; the column
+// indices do not depend on K).
+template <bool COLS>
 __global__ __launch_bounds__(kFillThreads) void csr_fill_kernel(ConvShape sh, const int *__restrict__ tab,
                                                                 const float *__restrict__ kernel,
                                                                 int *__restrict__ col_idx,
@@ -129,7 +132,7 @@ __global__ __launch_bounds__(kFillThreads) void csr_fill_kernel(ConvShape sh, co
     int *cdst = col_idx + (base - lead);
     float *vdst = vals + (base - lead);
     const long long nquads = (total + lead + 3) >> 2;
-    const bool aligned = (((uintptr_t)col_idx | (uintptr_t)vals) & 15u) == 0;
+    const bool aligned = (((COLS ? (uintptr_t)col_idx : 0) | (uintptr_t)vals) & 15u) == 0;
     for (long long quad = threadIdx.x; quad < nquads; quad += kFillThreads) {
         const long long qbeg = max(quad * 4 - lead, 0LL), qend = min(quad * 4 - lead + 4, total);
         // row and tap of the first entry
@@ -176,14 +179,14 @@ __global__ __launch_bounds__(kFillThreads) void csr_fill_kernel(ConvShape sh, co
             fvec4 vv;
             cv.x = cval[0]; cv.y = cval[1]; cv.z = cval[2]; cv.w = cval[3];
             vv.x = vval[0]; vv.y = vval[1]; vv.z = vval[2]; vv.w = vval[3];
-            __builtin_nontemporal_store(cv, reinterpret_cast<ivec4 *>(cdst + quad * 4));
+            if (COLS) __builtin_nontemporal_store(cv, reinterpret_cast<ivec4 *>(cdst + quad * 4));
             __builtin_nontemporal_store(vv, reinterpret_cast<fvec4 *>(vdst + quad * 4));
         } else {
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const long long q = quad * 4 - lead + e;
                 if (q >= qbeg && q < qend) {
-                    cdst[quad * 4 + e] = cval[e];
+                    if (COLS) cdst[quad * 4 + e] = cval[e];
                     vdst[quad * 4 + e] = vval[e];
                 }
             }

@@ -60,7 +60,7 @@ struct conv_plan {
     int max_row_nnz;          // k*k
     const int *row_ptr;       // borrowed, device
     const int *col_idx;       // borrowed, device
-    const float *vals;        // borrowed, device
+    float *vals;              // borrowed, device (rewritten by conv_update_kernel)
     int *axis_tab;            // owned, device: P1[0..m_out], P2[0..n_out]
     int device;
 };
@@ -133,7 +133,7 @@ int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, i
     axis_prefix_kernel<<<2, kAxisThreads, 0, q>>>(plan->shape, plan->axis_tab);
     row_ptr_kernel<<<(unsigned)rp_blocks, kRowPtrThreads, 0, q>>>(plan->shape, plan->axis_tab, row_ptr_dev);
     if (nnz > 0)
-        csr_fill_kernel<<<(unsigned)fill_blocks, kFillThreads, 0, q>>>(plan->shape, plan->axis_tab, kernel_dev,
+        csr_fill_kernel<true><<<(unsigned)fill_blocks, kFillThreads, 0, q>>>(plan->shape, plan->axis_tab, kernel_dev,
                                                                          col_idx_dev, vals_dev);
     if (!hip_ok(hipGetLastError())) {
         (void)hipFree(plan->axis_tab);
@@ -141,6 +141,16 @@ int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, i
         return CONV_EHIP;
     }
     *plan_out = plan;
+    return CONV_OK;
+}
+
+int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream) {
+    if (!plan || !kernel_dev) return CONV_ENULL;
+    if (plan->nnz == 0) return CONV_OK;
+    const int64_t fill_blocks = (int64_t)plan->shape.m_out * ((plan->shape.n_out + kFillRows - 1) / kFillRows);
+    csr_fill_kernel<false><<<(unsigned)fill_blocks, kFillThreads, 0, (hipStream_t)stream>>>(
+        plan->shape, plan->axis_tab, kernel_dev, nullptr, plan->vals);
+    if (!hip_ok(hipGetLastError())) return CONV_EHIP;
     return CONV_OK;
 }
 
@@ -489,6 +499,94 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
     }
     if (!hip_ok(hipGetLastError())) return CONV_EHIP;
     return CONV_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Many small products in one launch
+// ---------------------------------------------------------------------------
+}  // extern "C"
+
+struct conv_multi {
+    int n, batch, device;
+    unsigned blocks;
+    MultiDesc *descs_dev;     // owned, device
+};
+
+extern "C" {
+
+int conv_multi_create(int n, const conv_plan *const *plans, const float *const *x_dev, float *const *y_dev,
+                      int batch, conv_multi **multi_out) {
+    if (!multi_out) return CONV_ENULL;
+    *multi_out = nullptr;
+    if (!plans || !x_dev || !y_dev) return CONV_ENULL;
+    if (n < 1 || batch < 1) return CONV_EINVAL;
+    MultiDesc *host = new (std::nothrow) MultiDesc[n];
+    if (!host) return CONV_ENOMEM;
+    int64_t blocks = 0;
+    int status = CONV_OK;
+    for (int i = 0; i < n && status == CONV_OK; ++i) {
+        const conv_plan *p = plans[i];
+        if (!p || !x_dev[i] || !y_dev[i]) { status = CONV_ENULL; break; }
+        if (p->device != plans[0]->device) { status = CONV_EINVAL; break; }
+        const char *xb = (const char *)x_dev[i], *xe = xb + sizeof(float) * (size_t)p->cols * batch;
+        const char *yb = (const char *)y_dev[i], *ye = yb + sizeof(float) * (size_t)p->rows * batch;
+        if (xb < ye && yb < xe) { status = CONV_EALIAS; break; }
+        int gs = 0;
+        while ((1 << gs) < group_width(p->max_row_nnz)) ++gs;
+        host[i] = MultiDesc{p->row_ptr, p->col_idx, p->vals, x_dev[i], y_dev[i], (int)p->rows, gs, (int)blocks, 0};
+        blocks += ((p->rows << gs) + kGatherThreads - 1) / kGatherThreads;
+        if (blocks > kInt32Limit) status = CONV_EOVERFLOW;
+    }
+    if (status != CONV_OK) {
+        delete[] host;
+        return status;
+    }
+    conv_multi *mu = new (std::nothrow) conv_multi;
+    if (!mu) {
+        delete[] host;
+        return CONV_ENOMEM;
+    }
+    mu->n = n;
+    mu->batch = batch;
+    mu->device = plans[0]->device;
+    mu->blocks = (unsigned)blocks;
+    mu->descs_dev = nullptr;
+    if (!hip_ok(hipMalloc((void **)&mu->descs_dev, sizeof(MultiDesc) * (size_t)n))) {
+        delete mu;
+        delete[] host;
+        return CONV_ENOMEM;
+    }
+    const bool copied = hip_ok(hipMemcpy(mu->descs_dev, host, sizeof(MultiDesc) * (size_t)n, hipMemcpyHostToDevice));
+    delete[] host;
+    if (!copied) {
+        (void)hipFree(mu->descs_dev);
+        delete mu;
+        return CONV_EHIP;
+    }
+    *multi_out = mu;
+    return CONV_OK;
+}
+
+int conv_multi_apply(const conv_multi *multi, void *stream) {
+    if (!multi) return CONV_ENULL;
+    if (multi->blocks == 0) return CONV_OK;
+    const unsigned by = (unsigned)(multi->batch > 65535 ? 65535 : multi->batch);
+    spmm_multi_kernel<<<dim3(multi->blocks, by), kGatherThreads, 0, (hipStream_t)stream>>>(multi->descs_dev, multi->n,
+                                                                                            multi->batch);
+    if (!hip_ok(hipGetLastError())) return CONV_EHIP;
+    return CONV_OK;
+}
+
+int conv_multi_destroy(conv_multi *multi) {
+    if (!multi) return CONV_OK;
+    int st = CONV_OK;
+    int cur = 0;
+    const bool have = hip_ok(hipGetDevice(&cur));
+    if (have && cur != multi->device) (void)hipSetDevice(multi->device);
+    if (multi->descs_dev && !hip_ok(hipFree(multi->descs_dev))) st = CONV_EHIP;
+    if (have && cur != multi->device) (void)hipSetDevice(cur);
+    delete multi;
+    return st;
 }
 
 int conv_plan_shape(const conv_plan *plan, int *m, int *n, int *k, int *s, int *p, int *m_out, int *n_out,

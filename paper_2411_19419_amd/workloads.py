@@ -84,3 +84,14 @@ def densenet121_layer_shapes():
     shapes += [conv1(14), conv3(14)] * 24 + [conv1(14), pool2(14)]
     shapes += [conv1(7), conv3(7)] * 16
     return shapes
+
+
+def densenet121_sweep(batch: int = 1, seed: int = 121):
+    """The paper's experiment (Section 4.1): for every layer shape of Table 2 a
+    random-normal input and a random-normal kernel.  Yields (shape, x, K) per
+    layer, each layer with its own draws."""
+    for idx, (m, n, k, s, p) in enumerate(densenet121_layer_shapes()):
+        rng = np.random.default_rng([seed, idx])
+        x = rng.standard_normal(m * n * batch, dtype=np.float32)
+        K = rng.standard_normal(k * k, dtype=np.float32)
+        yield (m, n, k, s, p), x, K

@@ -322,3 +322,83 @@ def test_inf_and_nan_stay_in_their_rows(march_everywhere):
     want[29:32, 39:42, 2] = True
     assert np.array_equal(nonfinite, want)
     plan.close()
+
+
+def test_update_kernel_rewrites_vals_only():
+    """A new K for a built T: vals equal the oracle's enumeration with the new K
+    bit for bit, indices are untouched, and the apply follows."""
+    for shape, batch in [((96, 80, 7, 1, 3), 16), ((75, 75, 9, 3, 8), 4), ((33, 50, 2, 2, 0), 1), ((6, 6, 2, 1, 5), 4)]:
+        m, n, k, s, p = shape
+        x, K = _rand(shape, batch, 41)
+        K2 = np.random.default_rng(43).standard_normal(k * k).astype(np.float32)
+        plan = build_plan(shape, K)
+        rp_before, ci_before = plan.row_ptr.clone(), plan.col_idx.clone()
+        cs.conv_update_kernel(plan, torch.from_numpy(K2).to(device()))
+        torch.cuda.synchronize()
+        assert torch.equal(plan.row_ptr, rp_before) and torch.equal(plan.col_idx, ci_before)
+        check_csr(plan, shape, K2)
+        check_apply(plan, shape, K2, x, batch)
+        plan.close()
+
+
+@pytest.mark.parametrize("batch", [1, 3])
+def test_fused_layer_sweep_matches_oracle_layer_by_layer(batch):
+    """All 123 layer shapes of Table 2 in one launch (conv_multi_apply), each
+    output against the sliding-window oracle, and against conv_spmv on the same plan."""
+    layers = list(workloads.densenet121_sweep(batch=batch))
+    assert len(layers) == 123
+    plans = [build_plan(shape, K) for shape, _, K in layers]
+    xs = [torch.from_numpy(x).to(device()) for _, x, _ in layers]
+    ys = [torch.full((pl.rows * batch,), float("nan"), dtype=torch.float32, device=device()) for pl in plans]
+    multi = cs.ConvMulti(plans, xs, ys, batch=batch)
+    multi.apply()
+    torch.cuda.synchronize()
+    for (shape, x, K), pl, xd, y in zip(layers, plans, xs, ys):
+        m, n, k, s, p = shape
+        ref, scale = oracle.conv(m, n, k, s, p, x, K, batch=batch, want_scale=True)
+        got = y.cpu().numpy()
+        assert not np.any(np.isnan(got))
+        err = np.abs(got.astype(np.float64) - ref)
+        assert np.max(err / np.maximum(scale, 1e-30)) <= 1e-5, shape
+        single = cs.conv_spmv(pl, xd, batch=batch)
+        torch.cuda.synchronize()
+        assert np.max(np.abs(single.cpu().numpy().astype(np.float64) - ref) / np.maximum(scale, 1e-30)) <= 1e-5
+    multi.apply()                      # a second apply gives the same bits
+    torch.cuda.synchronize()
+    again = [y.clone() for y in ys]
+    multi.apply()
+    torch.cuda.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(again, ys))
+    multi.close()
+    for pl in plans:
+        pl.close()
+
+
+def test_fused_apply_mixed_shapes_and_errors():
+    shapes = [(40, 36, 5, 1, 2), (6, 6, 2, 1, 5), (1, 1, 1, 5, 2), (33, 20, 11, 2, 5), (50, 50, 13, 1, 6)]
+    batch = 2
+    plans, xs, ys, data = [], [], [], []
+    for i, shape in enumerate(shapes):
+        x, K = _rand(shape, batch, 50 + i)
+        plans.append(build_plan(shape, K))
+        xs.append(torch.from_numpy(x).to(device()))
+        ys.append(torch.full((plans[-1].rows * batch,), float("nan"), dtype=torch.float32, device=device()))
+        data.append((x, K))
+    multi = cs.ConvMulti(plans, xs, ys, batch=batch)
+    multi.apply()
+    torch.cuda.synchronize()
+    for shape, (x, K), y in zip(shapes, data, ys):
+        m, n, k, s, p = shape
+        ref, scale = oracle.conv(m, n, k, s, p, x, K, batch=batch, want_scale=True)
+        got = y.cpu().numpy()
+        assert not np.any(np.isnan(got))
+        empty = scale == 0
+        assert np.all(got[empty] == 0.0)
+        assert np.all(np.abs(got.astype(np.float64) - ref)[~empty] <= 1e-5 * scale[~empty])
+    multi.close()
+    with pytest.raises(cs.ConvError) as ei:       # x and y of one product overlap
+        buf = torch.zeros(plans[0].cols * batch + plans[0].rows * batch, device=device())
+        cs.ConvMulti([plans[0]], [buf[:plans[0].cols * batch]], [buf[8:8 + plans[0].rows * batch]], batch=batch)
+    assert ei.value.status == -6
+    for pl in plans:
+        pl.close()

@@ -84,6 +84,16 @@ def test_argument_validation_without_a_gpu():
     assert lib.conv_plan_shape(None, *([None] * 8)) == -2
     assert lib.conv_spmv_variant(None, 1) is None
     assert lib.conv_plan_destroy(None) == 0
+    assert lib.conv_update_kernel(None, 16, None) == -2
+    m_out = ctypes.c_void_p()
+    assert lib.conv_multi_create(1, None, None, None, 1, ctypes.byref(m_out)) == -2
+    arr = (ctypes.c_void_p * 1)(None)
+    assert lib.conv_multi_create(0, arr, arr, arr, 1, ctypes.byref(m_out)) == -1
+    assert lib.conv_multi_create(1, arr, arr, arr, 0, ctypes.byref(m_out)) == -1
+    assert lib.conv_multi_create(1, arr, arr, arr, 1, ctypes.byref(m_out)) == -2 and m_out.value is None
+    assert lib.conv_multi_apply(None, None) == -2
+    assert lib.conv_multi_destroy(None) == 0
+    assert lib.conv_set_march_min_jobs(0) == -1
 
 
 def test_strerror_texts():
