@@ -54,6 +54,10 @@ def _load():
             lib.oracle_csr.restype = i64
             lib.oracle_conv.argtypes = [i] * 6 + [vp, vp, vp, vp]
             lib.oracle_conv.restype = i
+            lib.oracle_csc.argtypes = [i] * 5 + [vp, vp, vp, vp, i64]
+            lib.oracle_csc.restype = i64
+            lib.oracle_conv_t.argtypes = [i] * 6 + [vp, vp, vp, vp]
+            lib.oracle_conv_t.restype = i
             _lib = lib
     return _lib
 
@@ -128,4 +132,37 @@ def conv(m, n, k, s, p, A, K, batch: int = 1, want_scale: bool = False):
                              out.ctypes.data, scale.ctypes.data if want_scale else None)
     if rc != 0:
         raise ValueError("oracle_conv failed (%d)" % rc)
+    return (out, scale) if want_scale else out
+
+
+def csc(m, n, k, s, p, K):
+    """(col_ptr int64[cols+1], row_idx int64[nnz], vals float32[nnz]): T column-compressed,
+    rows ascending inside a column; equally the CSR arrays of T^T."""
+    K = _f32(K).reshape(k * k)
+    mo, no = out_shape(m, n, k, s, p)
+    cap = mo * no * k * k
+    col_ptr = np.empty(m * n + 1, dtype=np.int64)
+    row_idx = np.empty(cap, dtype=np.int64)
+    vals = np.empty(cap, dtype=np.float32)
+    nnz = int(_load().oracle_csc(m, n, k, s, p, K.ctypes.data, col_ptr.ctypes.data,
+                                 row_idx.ctypes.data, vals.ctypes.data, cap))
+    if nnz < 0:
+        raise ValueError("oracle_csc failed (%d)" % nnz)
+    return col_ptr, row_idx[:nnz].copy(), vals[:nnz].copy()
+
+
+def conv_t(m, n, k, s, p, U, K, batch: int = 1, want_scale: bool = False):
+    """z = T^T u (the adjoint of the padded, strided convolution).  U: (m_out*n_out*batch,)
+    batch-minor float32.  Returns z (m*n*batch,) float32 and optionally the sums of |K||u|."""
+    U = _f32(U).reshape(-1)
+    K = _f32(K).reshape(k * k)
+    mo, no = out_shape(m, n, k, s, p)
+    if U.size != mo * no * batch:
+        raise ValueError("U has %d elements, expected %d" % (U.size, mo * no * batch))
+    out = np.empty(m * n * batch, dtype=np.float32)
+    scale = np.empty(m * n * batch, dtype=np.float64) if want_scale else None
+    rc = _load().oracle_conv_t(m, n, k, s, p, batch, U.ctypes.data, K.ctypes.data,
+                               out.ctypes.data, scale.ctypes.data if want_scale else None)
+    if rc != 0:
+        raise ValueError("oracle_conv_t failed (%d)" % rc)
     return (out, scale) if want_scale else out

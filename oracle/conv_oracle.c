@@ -192,3 +192,87 @@ int oracle_conv(int m, int n, int k, int s, int p, int B,
     free(Apad);
     return 0;
 }
+
+/* ------------------------------------------------------------------------
+ * The transposed transformation.  The paper's experiments also store T
+ * column-compressed (CSC, Section 3 and Section 4.1); the CSC arrays of T are
+ * the CSR arrays of T^T, and T^T = P^T C^T applied to a vector u of output
+ * size is the adjoint of the convolution: C^T scatters K[a][b] * u[x][y] onto
+ * padded position (s x + a, s y + b), P^T keeps the part of the padded plane
+ * that holds A (drops the border).
+ * ------------------------------------------------------------------------ */
+
+/* CSC of T = CSR of T^T, by transposing the enumerated CSR with a stable
+ * counting sort: entries are visited in row-major order of T, so inside a
+ * column they come out in ascending row order.  col_ptr has m*n + 1 entries,
+ * row_idx and vals need nnz entries.  Returns nnz or a negative status. */
+int64_t oracle_csc(int m, int n, int k, int s, int p, const float *K,
+                   int64_t *col_ptr, int64_t *row_idx, float *vals, int64_t cap)
+{
+    int64_t mo, no;
+    if (oracle_out_shape(m, n, k, s, p, &mo, &no) != 0) return -1;
+    int64_t rows = mo * no, cols = (int64_t)m * n;
+    int64_t *cbuf = (int64_t *)malloc(sizeof(int64_t) * (size_t)k * k);
+    float *vbuf = (float *)malloc(sizeof(float) * (size_t)k * k);
+    int64_t *next = (int64_t *)calloc((size_t)cols + 1, sizeof(int64_t));
+    if (!cbuf || !vbuf || !next) { free(cbuf); free(vbuf); free(next); return -2; }
+    for (int64_t r = 0; r < rows; ++r) {                  /* count per column */
+        int64_t c = oracle_csr_row(m, n, k, s, p, K, r, cbuf, vbuf);
+        for (int64_t e = 0; e < c; ++e) next[cbuf[e] + 1] += 1;
+    }
+    col_ptr[0] = 0;
+    for (int64_t j = 0; j < cols; ++j) col_ptr[j + 1] = col_ptr[j] + next[j + 1];
+    int64_t nnz = col_ptr[cols];
+    if (nnz > cap) { free(cbuf); free(vbuf); free(next); return -3; }
+    for (int64_t j = 0; j < cols; ++j) next[j] = col_ptr[j];
+    for (int64_t r = 0; r < rows; ++r) {                  /* place, rows ascending */
+        int64_t c = oracle_csr_row(m, n, k, s, p, K, r, cbuf, vbuf);
+        for (int64_t e = 0; e < c; ++e) {
+            int64_t at = next[cbuf[e]]++;
+            row_idx[at] = r;
+            vals[at] = vbuf[e];
+        }
+    }
+    free(cbuf); free(vbuf); free(next);
+    return nnz;
+}
+
+/* z = T^T u by definition: scatter every tap of every window onto a padded
+ * plane of doubles, then crop the border.
+ *   U     : m_out*n_out*B floats, batch-minor.
+ *   out   : m*n*B floats, batch-minor.
+ *   scale : optional, m*n*B doubles: the same sums with absolute values.
+ * Parallel over batch columns only (each column has its own plane); every
+ * output is summed in a fixed order. */
+int oracle_conv_t(int m, int n, int k, int s, int p, int B,
+                  const float *U, const float *K, float *out, double *scale)
+{
+    int64_t mo, no;
+    if (B < 1 || oracle_out_shape(m, n, k, s, p, &mo, &no) != 0) return -1;
+    int64_t H = (int64_t)m + 2 * p, W = (int64_t)n + 2 * p;
+    int fail = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t c = 0; c < B; ++c) {
+        double *plane = (double *)calloc((size_t)(H * W), sizeof(double));
+        double *mag = (double *)calloc((size_t)(H * W), sizeof(double));
+        if (!plane || !mag) { fail = 1; free(plane); free(mag); continue; }
+        for (int64_t x = 0; x < mo; ++x)
+            for (int64_t y = 0; y < no; ++y) {
+                double uv = (double)U[(x * no + y) * B + c];
+                for (int64_t a = 0; a < k; ++a)
+                    for (int64_t b = 0; b < k; ++b) {
+                        double kv = (double)K[a * k + b];
+                        plane[(s * x + a) * W + (s * y + b)] += kv * uv;
+                        mag[(s * x + a) * W + (s * y + b)] += fabs(kv) * fabs(uv);
+                    }
+            }
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t j = 0; j < n; ++j) {
+                out[(i * n + j) * B + c] = (float)plane[(i + p) * W + (j + p)];
+                if (scale) scale[(i * n + j) * B + c] = mag[(i + p) * W + (j + p)];
+            }
+        free(plane);
+        free(mag);
+    }
+    return fail ? -2 : 0;
+}
