@@ -74,6 +74,25 @@ int conv_csr_build(int m, int n, int k, int s, int p,
                    int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev,
                    void *stream, conv_plan **plan_out);
 
+/* Build T column-compressed (CSC), the other storage the paper uses
+ * (Sections 3 and 4.1).  The CSC arrays of T are the CSR arrays of T^T:
+ *   col_ptr_dev : (m*n + 1) int32, device, written.
+ *   row_idx_dev : nnz int32, device, written: rows x*n_out + y of T, ascending
+ *                 inside a column.
+ *   vals_dev    : nnz fp32, device, written: K[i+p-s*x][j+p-s*y] for column
+ *                 (i, j) and row (x, y).
+ * Column (i, j) has q1(i)*q2(j) entries, q1(i) = number of window lines x in
+ * [0, m_out) with 0 <= i+p-s*x < k (the same product structure as the rows of
+ * T in Theorem 2.1, with windows and pixels exchanged).  Everything else is
+ * as for conv_csr_build.  The plan returned is a plan for T^T: conv_spmv on it
+ * takes x_dev of m_out*n_out*batch elements and writes y_dev of m*n*batch
+ * elements, y = T^T x (the adjoint of the convolution: its input gradient);
+ * conv_update_kernel and conv_multi_create accept it as well. */
+int conv_csc_build(int m, int n, int k, int s, int p,
+                   const float *kernel_dev,
+                   int32_t *col_ptr_dev, int32_t *row_idx_dev, float *vals_dev,
+                   void *stream, conv_plan **plan_out);
+
 /* Replace the kernel of a built T: rewrites the plan's vals array from a new
  * K of the same size (k*k fp32, row-major, device); row_ptr and col_idx do not
  * depend on K and are left alone.  The paper notes (Section 4.2) that the
@@ -96,9 +115,12 @@ int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream);
  * repeated calls give bit-identical results.  x and y must not overlap. */
 int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch, void *stream);
 
-/* Shape and size queries on a plan (host only). */
+/* Shape and size queries on a plan (host only).  conv_plan_is_transposed
+ * returns 1 for a plan made by conv_csc_build, 0 for conv_csr_build, < 0 on
+ * error. */
 int conv_plan_shape(const conv_plan *plan, int *m, int *n, int *k, int *s, int *p,
                     int *m_out, int *n_out, int64_t *nnz);
+int conv_plan_is_transposed(const conv_plan *plan);
 
 /* Name of the apply variant conv_spmv would launch for this batch with
  * 16-byte-aligned x and y (for reports), or NULL on bad arguments.  The text

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     ConvError,
     ConvMulti,
     ConvPlan,
+    conv_csc_build,
     conv_csr_build,
     conv_nnz,
     conv_out_shape,

@@ -21,6 +21,7 @@ EXPORTS = (
     "conv_spmv_variant", "conv_plan_destroy", "conv_strerror", "conv_last_hip_error",
     "conv_set_march_min_jobs", "conv_update_kernel",
     "conv_multi_create", "conv_multi_apply", "conv_multi_destroy",
+    "conv_csc_build", "conv_plan_is_transposed",
 )
 
 
@@ -53,6 +54,10 @@ def _load():
         lib.conv_nnz.restype = i64
         lib.conv_csr_build.argtypes = [i, i, i, i, i, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]
         lib.conv_csr_build.restype = i
+        lib.conv_csc_build.argtypes = [i, i, i, i, i, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]
+        lib.conv_csc_build.restype = i
+        lib.conv_plan_is_transposed.argtypes = [vp]
+        lib.conv_plan_is_transposed.restype = i
         lib.conv_spmv.argtypes = [vp, vp, vp, i, vp]
         lib.conv_spmv.restype = i
         lib.conv_plan_shape.argtypes = [vp, pi, pi, pi, pi, pi, pi, pi, pi64]
@@ -118,8 +123,9 @@ class ConvPlan:
     """A built T: the three CSR tensors (torch, device) plus the library's
     plan handle that borrows them."""
 
-    def __init__(self, handle, shape, out_shape, nnz, row_ptr, col_idx, vals, kernel):
+    def __init__(self, handle, shape, out_shape, nnz, row_ptr, col_idx, vals, kernel, transposed=False):
         self._handle = handle
+        self.transposed = transposed    # the arrays hold T^T (CSC of T): row_ptr is col_ptr, col_idx is row_idx
         self.m, self.n, self.k, self.s, self.p = shape
         self.m_out, self.n_out = out_shape
         self.nnz = nnz
@@ -128,11 +134,11 @@ class ConvPlan:
 
     @property
     def rows(self):
-        return self.m_out * self.n_out
+        return self.m * self.n if self.transposed else self.m_out * self.n_out
 
     @property
     def cols(self):
-        return self.m * self.n
+        return self.m_out * self.n_out if self.transposed else self.m * self.n
 
     def variant(self, batch: int) -> str:
         v = _load().conv_spmv_variant(self._handle, int(batch))
@@ -157,7 +163,12 @@ class ConvPlan:
             pass
 
 
-def conv_csr_build(m, n, k, s, p, kernel, stream=None) -> ConvPlan:
+def conv_csc_build(m, n, k, s, p, kernel, stream=None) -> ConvPlan:
+    """Build T column-compressed; the plan applies T^T (plan.row_ptr is col_ptr, plan.col_idx is row_idx)."""
+    return conv_csr_build(m, n, k, s, p, kernel, stream=stream, _transposed=True)
+
+
+def conv_csr_build(m, n, k, s, p, kernel, stream=None, _transposed=False) -> ConvPlan:
     """Build T on the device of `kernel` (a k*k float32 CUDA/HIP tensor)."""
     import torch
     lib = _load()
@@ -167,19 +178,20 @@ def conv_csr_build(m, n, k, s, p, kernel, stream=None) -> ConvPlan:
             and kernel.numel() == k * k):
         raise ValueError("kernel must be a contiguous float32 device tensor with k*k elements")
     dev = kernel.device
-    if nnz >= 2 ** 31 or mo * no >= 2 ** 31 - 1:
+    if nnz >= 2 ** 31 or mo * no >= 2 ** 31 - 1 or m * n >= 2 ** 31 - 1:
         raise ConvError(-3, "conv_csr_build%r" % ((m, n, k, s, p),))
-    row_ptr = torch.empty(mo * no + 1, dtype=torch.int32, device=dev)
+    row_ptr = torch.empty((m * n if _transposed else mo * no) + 1, dtype=torch.int32, device=dev)
     col_idx = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)[:nnz]
     vals = torch.empty(max(nnz, 1), dtype=torch.float32, device=dev)[:nnz]
     handle = ctypes.c_void_p()
     with torch.cuda.device(dev):
         sh, _ = _stream_handle(stream)
-        st = lib.conv_csr_build(m, n, k, s, p, kernel.data_ptr(), row_ptr.data_ptr(),
-                                col_idx.data_ptr(), vals.data_ptr(), sh, ctypes.byref(handle))
+        fn = lib.conv_csc_build if _transposed else lib.conv_csr_build
+        st = fn(m, n, k, s, p, kernel.data_ptr(), row_ptr.data_ptr(),
+                col_idx.data_ptr(), vals.data_ptr(), sh, ctypes.byref(handle))
     if st != 0:
-        raise ConvError(st, "conv_csr_build%r" % ((m, n, k, s, p),))
-    return ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, row_ptr, col_idx, vals, kernel)
+        raise ConvError(st, "%s%r" % ("conv_csc_build" if _transposed else "conv_csr_build", (m, n, k, s, p)))
+    return ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, row_ptr, col_idx, vals, kernel, transposed=_transposed)
 
 
 def conv_update_kernel(plan: ConvPlan, kernel, stream=None) -> None:

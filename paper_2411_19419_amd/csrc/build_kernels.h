@@ -12,6 +12,15 @@
 // (a_lo + t / r2, b_lo + t % r2), which lands on input pixel
 // (s x + a - p, s y + b - p) (Section 2: C places K[a][b] at padded position
 // (s x + a, s y + b), P maps input (i, j) to padded (i + p, j + p)).
+//
+// The transposed matrix T^T (whose CSR arrays are the CSC arrays of T, the
+// other storage the paper uses, Sections 3 and 4.1) has the same product
+// structure with the roles of windows and pixels exchanged: row (i, j) of T^T
+// has q1(i) * q2(j) entries, q1(i) = number of window lines x in [0, m_out)
+// with 0 <= i + p - s x < k, its entries are the windows (x_lo + d1, y_lo + d2)
+// in ascending order with value K[i + p - s x][j + p - s y].  The kernels below
+// take a flag TR and build either matrix: "line" and "position in the line"
+// mean (x, y) for T and (i, j) for T^T.
 #pragma once
 #include "device_util.h"
 
@@ -33,22 +42,42 @@ __device__ __forceinline__ int axis_taps(int t, int extent, int k, int s, int p)
     return r > 0 ? (int)r : 0;
 }
 
+// Number of window positions t in [0, count_out) along one axis whose window
+// covers input coordinate i (0 <= i + p - s t < k), and the first of them.
+__device__ __forceinline__ int axis_first_window(int i, int k, int s, int p) {
+    const long long num = (long long)i + p - k + 1;          // smallest s*t allowed, may be negative
+    return num > 0 ? (int)((num + s - 1) / s) : 0;
+}
+__device__ __forceinline__ int axis_cover(int i, int count_out, int k, int s, int p) {
+    const long long lo = axis_first_window(i, k, s, p);
+    long long hi = ((long long)i + p) / s;
+    if (hi > count_out - 1) hi = count_out - 1;
+    return hi >= lo ? (int)(hi - lo + 1) : 0;
+}
+
+// Lines of the matrix being built and rows per line.
+template <bool TR> __device__ __forceinline__ int build_lines(const ConvShape &sh) { return TR ? sh.m : sh.m_out; }
+template <bool TR> __device__ __forceinline__ int build_per_line(const ConvShape &sh) { return TR ? sh.n : sh.n_out; }
+
 // One block per axis (blockIdx.x = 0: the m axis -> P1, 1: the n axis -> P2).
 // tab holds P1[0..m_out] followed by P2[0..n_out].  The block walks its axis
 // in chunks of blockDim.x with a running carry; inside a chunk an inclusive
 // scan runs over LDS (Hillis-Steele).
 constexpr int kAxisThreads = 1024;
 
+template <bool TR>
 __global__ __launch_bounds__(kAxisThreads) void axis_prefix_kernel(ConvShape sh, int *__restrict__ tab) {
     __shared__ int buf[2][kAxisThreads];
     const bool second = blockIdx.x == 1;
-    const int extent = second ? sh.n : sh.m;
-    const int count = second ? sh.n_out : sh.m_out;
-    int *out = second ? tab + (sh.m_out + 1) : tab;
+    const int extent = second ? sh.n : sh.m;                  // input extent along this axis
+    const int count_out = second ? sh.n_out : sh.m_out;       // window positions along this axis
+    const int count = TR ? extent : count_out;                // table length - 1
+    int *out = second ? tab + (build_lines<TR>(sh) + 1) : tab;
     int carry = 0;
     for (int base = 0; base < count; base += kAxisThreads) {
         const int t = base + (int)threadIdx.x;
-        const int mine = t < count ? axis_taps(t, extent, sh.k, sh.s, sh.p) : 0;
+        const int mine = t >= count ? 0 : (TR ? axis_cover(t, count_out, sh.k, sh.s, sh.p)
+                                                : axis_taps(t, extent, sh.k, sh.s, sh.p));
         int cur = 0;
         buf[0][threadIdx.x] = mine;
         __syncthreads();
@@ -70,18 +99,19 @@ __global__ __launch_bounds__(kAxisThreads) void axis_prefix_kernel(ConvShape sh,
 // row_ptr from the two axis tables; one thread per row, plus the final entry.
 constexpr int kRowPtrThreads = 256;
 
+template <bool TR>
 __global__ __launch_bounds__(kRowPtrThreads) void row_ptr_kernel(ConvShape sh, const int *__restrict__ tab,
                                                                  int *__restrict__ row_ptr) {
-    const int *P1 = tab, *P2 = tab + (sh.m_out + 1);
-    const int blocks_per_line = (sh.n_out + kRowPtrThreads - 1) / kRowPtrThreads;
+    const int L1 = build_lines<TR>(sh), L2 = build_per_line<TR>(sh);
+    const int *P1 = tab, *P2 = tab + (L1 + 1);
+    const int blocks_per_line = (L2 + kRowPtrThreads - 1) / kRowPtrThreads;
     const int x = blockIdx.x / blocks_per_line;
     const int y = (blockIdx.x - x * blocks_per_line) * kRowPtrThreads + (int)threadIdx.x;
-    if (y >= sh.n_out) return;
-    const long long S2 = P2[sh.n_out];
+    if (y >= L2) return;
+    const long long S2 = P2[L2];
     const long long p1 = P1[x], r1 = P1[x + 1] - P1[x];
-    row_ptr[(long long)x * sh.n_out + y] = (int)(p1 * S2 + r1 * P2[y]);
-    if (x == sh.m_out - 1 && y == sh.n_out - 1)
-        row_ptr[(long long)sh.m_out * sh.n_out] = (int)((long long)P1[sh.m_out] * S2);
+    row_ptr[(long long)x * L2 + y] = (int)(p1 * S2 + r1 * P2[y]);
+    if (x == L1 - 1 && y == L2 - 1) row_ptr[(long long)L1 * L2] = (int)((long long)P1[L1] * S2);
 }
 
 // col_idx and vals.  A block takes kFillRows consecutive rows of one output
@@ -101,8 +131,8 @@ constexpr int kFillThreads = 256;
 constexpr int kFillRows = 256;
 
 // COLS = false rewrites vals only (a new kernel for the same shape; the column
-// indices do not depend on K).
-template <bool COLS>
+// indices do not depend on K).  TR builds T^T.
+template <bool COLS, bool TR>
 __global__ __launch_bounds__(kFillThreads) void csr_fill_kernel(ConvShape sh, const int *__restrict__ tab,
                                                                 const float *__restrict__ kernel,
                                                                 int *__restrict__ col_idx,
@@ -110,22 +140,42 @@ __global__ __launch_bounds__(kFillThreads) void csr_fill_kernel(ConvShape sh, co
     typedef int ivec4 __attribute__((ext_vector_type(4)));
     typedef float fvec4 __attribute__((ext_vector_type(4)));
     __shared__ int rel[kFillRows + 1];           // P2[ya + i] - P2[ya]
-    const int *P1 = tab, *P2 = tab + (sh.m_out + 1);
-    const int blocks_per_line = (sh.n_out + kFillRows - 1) / kFillRows;
+    const int L1 = build_lines<TR>(sh), L2 = build_per_line<TR>(sh);
+    const int *P1 = tab, *P2 = tab + (L1 + 1);
+    const int blocks_per_line = (L2 + kFillRows - 1) / kFillRows;
     const int x = blockIdx.x / blocks_per_line;
     const int ya = (blockIdx.x - x * blocks_per_line) * kFillRows;
-    const int nrows = min(kFillRows, sh.n_out - ya);
+    const int nrows = min(kFillRows, L2 - ya);
     const int p1 = P1[x], r1 = P1[x + 1] - p1;
     const int p2a = P2[ya];
     for (int i = threadIdx.x; i <= nrows; i += kFillThreads) rel[i] = P2[ya + i] - p2a;
     __syncthreads();
-    const long long base = (long long)p1 * P2[sh.n_out] + (long long)r1 * p2a;
+    const long long base = (long long)p1 * P2[L2] + (long long)r1 * p2a;
     const long long total = (long long)r1 * rel[nrows];
     if (total == 0) return;                      // uniform: these rows have no entries
+    // Along the line axis: first stored kernel row a_lo and its input line i0 (T), or the
+    // first covering window line x_lo (T^T).  first2 does the same along the other axis.
     const long long sx = (long long)sh.s * x;
-    const int a_lo = sx < sh.p ? (int)(sh.p - sx) : 0;
-    const long long i0 = sx + a_lo - sh.p;       // input line of the rows' first stored tap
-    const float inv_r1 = 1.0f / (float)r1, inv_k = 1.0f / (float)sh.k;
+    const int a_lo = TR ? axis_first_window(x, sh.k, sh.s, sh.p) : (sx < sh.p ? (int)(sh.p - sx) : 0);
+    const long long i0 = sx + a_lo - sh.p;
+    auto first2 = [&](int u2) {
+        if (TR) return axis_first_window(u2, sh.k, sh.s, sh.p);
+        const long long sy = (long long)sh.s * u2;
+        return sy < sh.p ? (int)(sh.p - sy) : 0;
+    };
+    // column index and kernel index of entry (da, db) of the row at position u2 with first2 = b_lo
+    auto entry = [&](int u2, int b_lo, int da, int db, int &col, int &kidx) {
+        if (TR) {
+            const int wx = a_lo + da, wy = b_lo + db;          // window (wx, wy) covers pixel (x, u2)
+            col = (int)((long long)wx * sh.n_out + wy);
+            kidx = (x + sh.p - sh.s * wx) * sh.k + (u2 + sh.p - sh.s * wy);
+        } else {
+            col = (int)((i0 + da) * sh.n + ((long long)sh.s * u2 + b_lo - sh.p) + db);
+            kidx = (a_lo + da) * sh.k + (b_lo + db);
+        }
+    };
+    const int full2 = TR ? (sh.k + sh.s - 1) / sh.s : sh.k;   // most entries a row has along the second axis
+    const float inv_r1 = 1.0f / (float)r1, inv_k = 1.0f / (float)full2;
     const bool small = total < (1 << 21);        // float-reciprocal division is exact below 2^21
     // quads are aligned in the arrays: span position q sits in quad (q + lead) / 4
     const int lead = (int)(base & 3);
@@ -137,7 +187,7 @@ __global__ __launch_bounds__(kFillThreads) void csr_fill_kernel(ConvShape sh, co
         const long long qbeg = max(quad * 4 - lead, 0LL), qend = min(quad * 4 - lead + 4, total);
         // row and tap of the first entry
         const int u = small ? div_small((int)qbeg, inv_r1) : (int)(qbeg / r1);   // tap columns before its row
-        int yy = small ? div_small(u, inv_k) : u / sh.k;
+        int yy = small ? div_small(u, inv_k) : u / full2;
         yy = min(yy, nrows - 1);
         if (!(rel[yy] <= u && u < rel[yy + 1])) {                               // rows before it were not all full
             int lo = 0, hi = nrows;                                              // rel[lo] <= u < rel[hi]
@@ -150,8 +200,7 @@ __global__ __launch_bounds__(kFillThreads) void csr_fill_kernel(ConvShape sh, co
         int r2 = rel[yy + 1] - rel[yy];
         const int t = (int)(qbeg - (long long)r1 * rel[yy]);                    // 0 <= t < r1*r2
         int da = small ? div_small(t, __builtin_amdgcn_rcpf((float)r2)) : t / r2, db = t - da * r2;
-        long long sy = (long long)sh.s * (ya + yy);
-        int b_lo = sy < sh.p ? (int)(sh.p - sy) : 0;
+        int b_lo = first2(ya + yy);
         int cval[4];
         float vval[4];
 #pragma unroll
@@ -160,16 +209,16 @@ __global__ __launch_bounds__(kFillThreads) void csr_fill_kernel(ConvShape sh, co
             cval[e] = 0;
             vval[e] = 0.0f;
             if (q >= qbeg && q < qend) {
-                cval[e] = (int)((i0 + da) * sh.n + (sy + b_lo - sh.p) + db);
-                vval[e] = kernel[(a_lo + da) * sh.k + (b_lo + db)];
+                int kidx;
+                entry(ya + yy, b_lo, da, db, cval[e], kidx);
+                vval[e] = kernel[kidx];
                 if (++db == r2) {                // next kernel row, or the next row of T that has entries
                     db = 0;
                     if (++da == r1 && q + 1 < qend) {
                         da = 0;
                         do { ++yy; } while (rel[yy + 1] == rel[yy]);
                         r2 = rel[yy + 1] - rel[yy];
-                        sy = (long long)sh.s * (ya + yy);
-                        b_lo = sy < sh.p ? (int)(sh.p - sy) : 0;
+                        b_lo = first2(ya + yy);
                     }
                 }
             }

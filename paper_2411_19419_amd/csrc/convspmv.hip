@@ -61,8 +61,9 @@ struct conv_plan {
     const int *row_ptr;       // borrowed, device
     const int *col_idx;       // borrowed, device
     float *vals;              // borrowed, device (rewritten by conv_update_kernel)
-    int *axis_tab;            // owned, device: P1[0..m_out], P2[0..n_out]
+    int *axis_tab;            // owned, device: the two per-axis prefix tables of the build
     int device;
+    bool transposed;          // the arrays hold T^T (CSC of T): rows = m*n, cols = m_out*n_out
 };
 
 extern "C" {
@@ -89,8 +90,13 @@ int64_t conv_nnz(int m, int n, int k, int s, int p) {
     return total;
 }
 
-int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *row_ptr_dev,
-                   int32_t *col_idx_dev, float *vals_dev, void *stream, conv_plan **plan_out) {
+}  // extern "C"
+
+namespace {
+
+template <bool TR>
+int build_impl(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *ptr_dev, int32_t *idx_dev,
+               float *vals_dev, void *stream, conv_plan **plan_out) {
     if (!plan_out) return CONV_ENULL;
     *plan_out = nullptr;
     int64_t mo, no;
@@ -98,16 +104,19 @@ int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, i
     if (st != CONV_OK) return st;
     const int64_t nnz = conv_nnz(m, n, k, s, p);
     if (nnz < 0) return (int)nnz;
-    const int64_t rows = mo * no, cols = (int64_t)m * n;
-    // 32-bit indices: entries, columns, rows (+1 for row_ptr), the per-axis
+    const int64_t out_pixels = mo * no, in_pixels = (int64_t)m * n;
+    const int64_t rows = TR ? in_pixels : out_pixels, cols = TR ? out_pixels : in_pixels;
+    const int64_t l1 = TR ? m : mo, l2 = TR ? n : no;        // lines of the matrix, rows per line
+    // 32-bit indices: entries, columns, rows (+1 for the pointer array), the per-axis
     // prefix sums, and the grids of the build kernels.
-    if (nnz > kInt32Limit || cols > kInt32Limit || rows >= kInt32Limit || (int64_t)k * k > kInt32Limit ||
-        mo * (int64_t)k > kInt32Limit || no * (int64_t)k > kInt32Limit)
+    if (nnz > kInt32Limit || in_pixels >= kInt32Limit || out_pixels >= kInt32Limit || (int64_t)k * k > kInt32Limit ||
+        mo * (int64_t)k > kInt32Limit || no * (int64_t)k > kInt32Limit || (int64_t)m * k > kInt32Limit ||
+        (int64_t)n * k > kInt32Limit)
         return CONV_EOVERFLOW;
-    const int64_t fill_blocks = mo * ((no + kFillRows - 1) / kFillRows);
-    const int64_t rp_blocks = mo * ((no + kRowPtrThreads - 1) / kRowPtrThreads);
+    const int64_t fill_blocks = l1 * ((l2 + kFillRows - 1) / kFillRows);
+    const int64_t rp_blocks = l1 * ((l2 + kRowPtrThreads - 1) / kRowPtrThreads);
     if (fill_blocks > kInt32Limit || rp_blocks > kInt32Limit) return CONV_EOVERFLOW;
-    if (!row_ptr_dev || !kernel_dev || (nnz > 0 && (!col_idx_dev || !vals_dev))) return CONV_ENULL;
+    if (!ptr_dev || !kernel_dev || (nnz > 0 && (!idx_dev || !vals_dev))) return CONV_ENULL;
 
     conv_plan *plan = new (std::nothrow) conv_plan;
     if (!plan) return CONV_ENOMEM;
@@ -115,26 +124,28 @@ int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, i
     plan->rows = rows;
     plan->cols = cols;
     plan->nnz = nnz;
-    plan->max_row_nnz = k * k;
-    plan->row_ptr = row_ptr_dev;
-    plan->col_idx = col_idx_dev;
+    const int per_axis = TR ? (k + s - 1) / s : k;
+    plan->max_row_nnz = per_axis * per_axis;
+    plan->row_ptr = ptr_dev;
+    plan->col_idx = idx_dev;
     plan->vals = vals_dev;
     plan->axis_tab = nullptr;
     plan->device = 0;
+    plan->transposed = TR;
     if (!hip_ok(hipGetDevice(&plan->device))) {
         delete plan;
         return CONV_EHIP;
     }
-    if (!hip_ok(hipMalloc((void **)&plan->axis_tab, sizeof(int) * (size_t)(mo + no + 2)))) {
+    if (!hip_ok(hipMalloc((void **)&plan->axis_tab, sizeof(int) * (size_t)(l1 + l2 + 2)))) {
         delete plan;
         return CONV_ENOMEM;
     }
     hipStream_t q = (hipStream_t)stream;
-    axis_prefix_kernel<<<2, kAxisThreads, 0, q>>>(plan->shape, plan->axis_tab);
-    row_ptr_kernel<<<(unsigned)rp_blocks, kRowPtrThreads, 0, q>>>(plan->shape, plan->axis_tab, row_ptr_dev);
+    axis_prefix_kernel<TR><<<2, kAxisThreads, 0, q>>>(plan->shape, plan->axis_tab);
+    row_ptr_kernel<TR><<<(unsigned)rp_blocks, kRowPtrThreads, 0, q>>>(plan->shape, plan->axis_tab, ptr_dev);
     if (nnz > 0)
-        csr_fill_kernel<true><<<(unsigned)fill_blocks, kFillThreads, 0, q>>>(plan->shape, plan->axis_tab, kernel_dev,
-                                                                         col_idx_dev, vals_dev);
+        csr_fill_kernel<true, TR><<<(unsigned)fill_blocks, kFillThreads, 0, q>>>(plan->shape, plan->axis_tab,
+                                                                               kernel_dev, idx_dev, vals_dev);
     if (!hip_ok(hipGetLastError())) {
         (void)hipFree(plan->axis_tab);
         delete plan;
@@ -144,12 +155,32 @@ int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, i
     return CONV_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *row_ptr_dev,
+                   int32_t *col_idx_dev, float *vals_dev, void *stream, conv_plan **plan_out) {
+    return build_impl<false>(m, n, k, s, p, kernel_dev, row_ptr_dev, col_idx_dev, vals_dev, stream, plan_out);
+}
+
+int conv_csc_build(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *col_ptr_dev,
+                   int32_t *row_idx_dev, float *vals_dev, void *stream, conv_plan **plan_out) {
+    return build_impl<true>(m, n, k, s, p, kernel_dev, col_ptr_dev, row_idx_dev, vals_dev, stream, plan_out);
+}
+
 int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream) {
     if (!plan || !kernel_dev) return CONV_ENULL;
     if (plan->nnz == 0) return CONV_OK;
-    const int64_t fill_blocks = (int64_t)plan->shape.m_out * ((plan->shape.n_out + kFillRows - 1) / kFillRows);
-    csr_fill_kernel<false><<<(unsigned)fill_blocks, kFillThreads, 0, (hipStream_t)stream>>>(
-        plan->shape, plan->axis_tab, kernel_dev, nullptr, plan->vals);
+    const int64_t l1 = plan->transposed ? plan->shape.m : plan->shape.m_out;
+    const int64_t l2 = plan->transposed ? plan->shape.n : plan->shape.n_out;
+    const unsigned fill_blocks = (unsigned)(l1 * ((l2 + kFillRows - 1) / kFillRows));
+    if (plan->transposed)
+        csr_fill_kernel<false, true><<<fill_blocks, kFillThreads, 0, (hipStream_t)stream>>>(
+            plan->shape, plan->axis_tab, kernel_dev, nullptr, plan->vals);
+    else
+        csr_fill_kernel<false, false><<<fill_blocks, kFillThreads, 0, (hipStream_t)stream>>>(
+            plan->shape, plan->axis_tab, kernel_dev, nullptr, plan->vals);
     if (!hip_ok(hipGetLastError())) return CONV_EHIP;
     return CONV_OK;
 }
@@ -312,6 +343,7 @@ ApplyChoice choose_apply(const conv_plan *plan, const float *x, const float *y, 
     c.nv = !vec ? 0 : (batch % 16 == 0 ? 4 : (batch % 8 == 0 ? 2 : 1));
     c.kind = vec ? Kind::GatherVec : Kind::GatherScalar;
     if (plan->nnz == 0 || (!vec && batch != 1) || (vec && batch / (4 * c.nv) > 65535)) return c;
+    if (plan->transposed) return c;      // the staged kernels are laid out for T; T^T takes the row-group kernels
 
     // marching kernel: float4 column chunks, or one scalar column for a single vector (SpMV)
     MarchShape ms;
@@ -602,6 +634,8 @@ int conv_plan_shape(const conv_plan *plan, int *m, int *n, int *k, int *s, int *
     if (nnz) *nnz = plan->nnz;
     return CONV_OK;
 }
+
+int conv_plan_is_transposed(const conv_plan *plan) { return plan ? (plan->transposed ? 1 : 0) : CONV_ENULL; }
 
 const char *conv_spmv_variant(const conv_plan *plan, int batch) {
     if (!plan || batch < 1) return nullptr;

@@ -54,3 +54,39 @@ def check_apply(plan, shape, K, x, batch, x_dev=None):
     assert scaled <= REL_TOL, "max err/scale %.3e" % scaled
     assert normwise <= REL_TOL, "normwise error %.3e" % normwise
     return scaled, normwise
+
+
+def build_plan_t(shape, K):
+    m, n, k, s, p = shape
+    return cs.conv_csc_build(m, n, k, s, p, torch.from_numpy(np.ascontiguousarray(K, dtype=np.float32)).to(device()))
+
+
+def check_csc(plan, shape, K):
+    """col_ptr, row_idx and vals of T column-compressed, bit-exact against the oracle."""
+    m, n, k, s, p = shape
+    cp, ri, va = oracle.csc(m, n, k, s, p, K)
+    assert plan.transposed and plan.nnz == len(ri) == oracle.nnz_closed(m, n, k, s, p)
+    assert np.array_equal(plan.row_ptr.cpu().numpy().astype(np.int64), cp), "col_ptr differs"
+    assert np.array_equal(plan.col_idx.cpu().numpy().astype(np.int64), ri), "row_idx differs"
+    assert np.array_equal(plan.vals.cpu().numpy().view(np.uint32), va.view(np.uint32)), "vals differ"
+
+
+def check_apply_t(plan, shape, K, u, batch):
+    """z = T^T u against the scatter-and-crop oracle."""
+    m, n, k, s, p = shape
+    z = torch.full((plan.rows * batch,), float("nan"), dtype=torch.float32, device=device())
+    cs.conv_spmv(plan, torch.from_numpy(u).to(device()), z, batch=batch)
+    torch.cuda.synchronize()
+    got = z.cpu().numpy()
+    ref, scale = oracle.conv_t(m, n, k, s, p, u, K, batch=batch, want_scale=True)
+    assert not np.any(np.isnan(got)), "some outputs were never written"
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    empty = scale == 0.0
+    if np.any(empty):
+        assert np.all(got[empty] == 0.0) and not np.any(np.signbit(got[empty]))
+    scaled = float(np.max(err[~empty] / scale[~empty])) if np.any(~empty) else 0.0
+    denom = float(np.max(np.abs(ref))) if ref.size else 0.0
+    normwise = float(np.max(err)) / denom if denom > 0 else 0.0
+    assert scaled <= REL_TOL, "max err/scale %.3e" % scaled
+    assert normwise <= REL_TOL, "normwise error %.3e" % normwise
+    return scaled, normwise

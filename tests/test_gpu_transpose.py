@@ -1,0 +1,116 @@
+"""GPU parity for the transposed side: T column-compressed (conv_csc_build) bit-exact
+against the oracle, and y = T^T x (conv_spmv on that plan) against the adjoint oracle."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2411_19419_amd as cs
+from paper_2411_19419_amd import workloads
+
+from gpu_util import build_plan, build_plan_t, check_apply_t, check_csc, device
+
+pytestmark = pytest.mark.gpu
+
+
+def _rand_t(shape, batch, seed):
+    m, n, k, s, p = shape
+    mo, no = oracle.out_shape(*shape)
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal(mo * no * batch).astype(np.float32),
+            rng.standard_normal(k * k).astype(np.float32))
+
+
+def test_transposed_exhaustive_tiny_grid():
+    batches = itertools.cycle([1, 3, 4, 8])
+    count = 0
+    for shape in itertools.product(range(1, 6), range(1, 6), range(1, 5), range(1, 4), range(0, 5)):
+        m, n, k, s, p = shape
+        if k > m + 2 * p or k > n + 2 * p:
+            continue
+        batch = next(batches)
+        u, K = _rand_t(shape, batch, count)
+        plan = build_plan_t(shape, K)
+        check_csc(plan, shape, K)
+        check_apply_t(plan, shape, K, u, batch)
+        plan.close()
+        count += 1
+    assert count > 1000
+
+
+@pytest.mark.parametrize("shape,batch", [
+    ((37, 53, 7, 1, 3), 16), ((130, 67, 7, 1, 3), 4), ((100, 90, 5, 2, 2), 16), ((33, 200, 3, 1, 1), 1),
+    ((75, 75, 9, 3, 8), 4), ((90, 141, 11, 4, 5), 2), ((40, 40, 13, 1, 6), 3), ((3, 50, 7, 2, 3), 5),
+    ((6, 6, 2, 1, 5), 7), ((1, 1, 1, 5, 2), 3), ((200, 1, 1, 1, 0), 6), ((300, 301, 2, 2, 0), 8),
+    ((257, 513, 3, 2, 1), 1), ((64, 1000, 5, 3, 1), 4),
+])
+def test_transposed_ragged_and_degenerate_shapes(shape, batch):
+    u, K = _rand_t(shape, batch, 7)
+    plan = build_plan_t(shape, K)
+    check_csc(plan, shape, K)
+    check_apply_t(plan, shape, K, u, batch)
+    plan.close()
+
+
+@pytest.mark.parametrize("shape", sorted(set(workloads.densenet121_layer_shapes())))
+def test_transposed_densenet_layer_shapes(shape):
+    u, K = _rand_t(shape, 4, 9)
+    plan = build_plan_t(shape, K)
+    check_csc(plan, shape, K)
+    check_apply_t(plan, shape, K, u, 4)
+    plan.close()
+
+
+@pytest.mark.parametrize("name", ["strided_256_k5_b64", "headline_1024_k7_b16", "padheavy_512_k9_s3",
+                                  "padheavy_4096_k11_s4_b4"])
+def test_transposed_named_workloads_full_size(name):
+    w = workloads.WORKLOADS[name]
+    batch = min(w.batch, 16)
+    u, K = _rand_t(w.shape, batch, 11)
+    plan = build_plan_t(w.shape, K)
+    check_csc(plan, w.shape, K)
+    scaled, normwise = check_apply_t(plan, w.shape, K, u, batch)
+    print("%s transposed: variant %s, max err/scale %.2e" % (name, plan.variant(batch), scaled))
+    plan.close()
+
+
+def test_adjoint_identity_on_the_device():
+    """<T x, u> = <x, T^T u> with both products from the GPU (integers: exact in fp32)."""
+    shape, batch = (60, 44, 5, 2, 2), 1
+    m, n, k, s, p = shape
+    mo, no = oracle.out_shape(*shape)
+    rng = np.random.default_rng(3)
+    K = rng.integers(-3, 4, size=k * k).astype(np.float32)
+    x = rng.integers(-4, 5, size=m * n).astype(np.float32)
+    u = rng.integers(-4, 5, size=mo * no).astype(np.float32)
+    fwd, bwd = build_plan(shape, K), build_plan_t(shape, K)
+    y = cs.conv_spmv(fwd, torch.from_numpy(x).to(device()), batch=batch)
+    z = cs.conv_spmv(bwd, torch.from_numpy(u).to(device()), batch=batch)
+    torch.cuda.synchronize()
+    lhs = float(np.dot(y.cpu().numpy().astype(np.float64), u))
+    rhs = float(np.dot(x.astype(np.float64), z.cpu().numpy().astype(np.float64)))
+    assert lhs == rhs
+    fwd.close()
+    bwd.close()
+
+
+def test_transposed_update_kernel_and_fused_apply():
+    shape, batch = (50, 40, 3, 2, 1), 2
+    u, K = _rand_t(shape, batch, 21)
+    K2 = np.random.default_rng(22).standard_normal(9).astype(np.float32)
+    plan = build_plan_t(shape, K)
+    cs.conv_update_kernel(plan, torch.from_numpy(K2).to(device()))
+    torch.cuda.synchronize()
+    check_csc(plan, shape, K2)
+    check_apply_t(plan, shape, K2, u, batch)
+    ud = torch.from_numpy(u).to(device())
+    z = torch.full((plan.rows * batch,), float("nan"), dtype=torch.float32, device=device())
+    multi = cs.ConvMulti([plan], [ud], [z], batch=batch)
+    multi.apply()
+    torch.cuda.synchronize()
+    ref, scale = oracle.conv_t(*shape, u, K2, batch=batch, want_scale=True)
+    assert np.all(np.abs(z.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * np.maximum(scale, 1e-30))
+    multi.close()
+    plan.close()
