@@ -26,7 +26,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 
 
-def cpu_baseline(w, x, K):
+def cpu_baseline(w, x, K, transposed=False):
     """The oracle as it stands, timed on the host cores on the whole workload
     (one call as warm-up, then the median of repeated calls within ~20 s)."""
     import numpy as np
@@ -37,7 +37,7 @@ def cpu_baseline(w, x, K):
     t_all = time.perf_counter()
     while len(times) < 5 and (time.perf_counter() - t_all < 20.0 or not times):
         t0 = time.perf_counter()
-        oracle.conv(m, n, k, s, p, x, K, batch=w.batch)
+        (oracle.conv_t if transposed else oracle.conv)(m, n, k, s, p, x, K, batch=w.batch)
         times.append(time.perf_counter() - t0)
     med = sorted(times)[len(times) // 2]
     nnz = oracle.nnz_closed(m, n, k, s, p)
@@ -192,6 +192,8 @@ def main():
     ap.add_argument("--workload", default=None,
                     help="name in workloads.WORKLOADS (default: the headline), or densenet121_sweep")
     ap.add_argument("--batch", type=int, default=1, help="batch of the densenet121_sweep workload")
+    ap.add_argument("--transposed", action="store_true",
+                    help="build T column-compressed and time y = T^T x (the adjoint) instead")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -215,12 +217,15 @@ def main():
     w = workloads.WORKLOADS[args.workload or workloads.HEADLINE]
     m, n, k, s, p = w.shape
     x_h, K_h = workloads.make(w)
+    if args.transposed:      # the operand of T^T has the size of the convolution's output
+        mo_, no_ = cs.conv_out_shape(m, n, k, s, p)
+        x_h = workloads.make_input(mo_, no_, w.batch, w.x_dist, w.seed + 100)
     x = torch.from_numpy(x_h).to(dev)
     K = torch.from_numpy(K_h).to(dev)
     stream = torch.cuda.current_stream()
 
     # ---- build (row_ptr + fill kernels; allocation of the CSR arrays excluded from the event time)
-    plan = cs.conv_csr_build(m, n, k, s, p, K)
+    plan = (cs.conv_csc_build if args.transposed else cs.conv_csr_build)(m, n, k, s, p, K)
     torch.cuda.synchronize()
     build_ms = []
     lib = cs.binding._load()
@@ -229,8 +234,9 @@ def main():
         h = ctypes.c_void_p()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
-        st = lib.conv_csr_build(m, n, k, s, p, K.data_ptr(), plan.row_ptr.data_ptr(), plan.col_idx.data_ptr(),
-                                plan.vals.data_ptr(), ctypes.c_void_p(stream.cuda_stream), ctypes.byref(h))
+        build_fn = lib.conv_csc_build if args.transposed else lib.conv_csr_build
+        st = build_fn(m, n, k, s, p, K.data_ptr(), plan.row_ptr.data_ptr(), plan.col_idx.data_ptr(),
+                      plan.vals.data_ptr(), ctypes.c_void_p(stream.cuda_stream), ctypes.byref(h))
         e1.record(stream)
         torch.cuda.synchronize()
         assert st == 0
@@ -314,7 +320,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "m": m, "n": n, "k": k, "s": s, "p": p, "batch": w.batch,
                    "nnz": plan.nnz, "rows": plan.rows, "cols": plan.cols,
-                   "apply_variant": plan.variant(w.batch), "streams": n_streams},
+                   "apply_variant": plan.variant(w.batch), "streams": n_streams,
+                   "matrix": "T^T (CSC of T)" if args.transposed else "T (CSR)"},
         "pct_of_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
         "useful_mac_per_s": plan.nnz * w.batch / (ms_per_step * 1e-3),
         "model_bytes": model_bytes,
@@ -328,7 +335,7 @@ def main():
                      "kernel_ms_median": kern_ms[len(kern_ms) // 2], "kernel_ms_min": kern_ms[0]},
     }
     if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(w, x_h, K_h)
+        out["cpu_baseline"] = cpu_baseline(w, x_h, K_h, args.transposed)
         out["gpu_over_cpu"] = out["useful_mac_per_s"] / 1e9 / out["cpu_baseline"]["value"]
     plan.close()
     print(json.dumps(out))

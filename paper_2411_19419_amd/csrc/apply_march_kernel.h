@@ -33,15 +33,21 @@ namespace convspmv {
 
 typedef float vec4 __attribute__((ext_vector_type(4)));
 
+// The same kernel applies T^T (built by conv_csc_build): there the operand is a vector of
+// output size, the result has input size, and result line i needs the operand lines
+// (window lines) x with 0 <= i + p - s x < k instead of the input lines of a window.
 struct MarchGeom {
-    int m, n, m_out, n_out, s, p, k;
+    int m, n;             // operand: lines and pixels per line (the image for T, the window grid for T^T)
+    int m_out, n_out;     // result: lines and pixels per line
+    int s, p, k;
+    int tr;               // 1: the matrix is T^T
     int batch;            // x / y row pitch, in floats
     int nnz;
     int strips;           // strips of TW output columns
     int seg;              // output lines per workgroup
     int segs;             // segments per strip
     int blocks_per_xcd;   // strips * segs split evenly over the XCDs (rounded up)
-    int iw;               // input columns a strip can touch: (TW-1)*s + k
+    int iw;               // operand columns a strip can touch (upper bound): (TW-1)*s + k, or (TW-2+k)/s + 2 for T^T
     int iw_pitch;         // LDS pixels per ring line (>= iw)
     float inv_n;          // 1.0f / n
 };
@@ -88,15 +94,23 @@ __global__ __launch_bounds__(512, 4) void spmm_march_kernel(const int *__restric
     const int gl = lane % G, gr = lane / G;
 
     // ---- input columns of the strip, clipped to the image
-    const int j_lo = g.s * y0 - g.p;
+    // first window position along an axis that covers coordinate t (T^T), never negative
+    auto first_window = [&](int t) {
+        const int num = t + g.p - g.k + 1;
+        return num > 0 ? (num + g.s - 1) / g.s : 0;
+    };
+    const int j_lo = g.tr ? first_window(y0) : g.s * y0 - g.p;
     const int j0 = min(max(j_lo, 0), g.n - 1);
     const int iwc = max(min(j_lo + g.iw, g.n) - j0, 0);
     const float inv_iwc = 1.0f / (float)max(iwc, 1);
     const int zslot = NL * g.iw_pitch;            // a pixel of zeros in every plane
 
     // first / one-past-last input line that output lines [xo, xo + cnt) can touch, clipped
-    auto line_lo = [&](int xo) { return min(max(g.s * xo - g.p, 0), g.m); };
-    auto line_hi = [&](int xo, int cnt) { return min(max(g.s * (xo + cnt - 1) - g.p + g.k, 0), g.m); };
+    auto line_lo = [&](int xo) { return min(max(g.tr ? first_window(xo) : g.s * xo - g.p, 0), g.m); };
+    auto line_hi = [&](int xo, int cnt) {
+        const int last = xo + cnt - 1;
+        return min(max(g.tr ? (last + g.p) / g.s + 1 : g.s * last - g.p + g.k, 0), g.m);
+    };
 
     // ---- per-lane row of T on output line xo: bounds, clamped so that every lane holds
     // valid, ascending entry indices (a lane without a row gets an empty range)

@@ -290,44 +290,56 @@ constexpr int kMarchTargetBlocks = 512;      // two resident workgroups on each 
 
 bool march_geometry(const conv_plan *plan, int batch, int nv, int tw, MarchGeom *out, int *ls_out, int *nl_out) {
     const ConvShape &sh = plan->shape;
+    const bool tr = plan->transposed;
     MarchGeom g{};
-    g.m = sh.m; g.n = sh.n; g.m_out = sh.m_out; g.n_out = sh.n_out; g.s = sh.s; g.p = sh.p; g.k = sh.k;
+    // operand and result grids: the image and the window grid for T, exchanged for T^T
+    g.m = tr ? sh.m_out : sh.m;
+    g.n = tr ? sh.n_out : sh.n;
+    g.m_out = tr ? sh.m : sh.m_out;
+    g.n_out = tr ? sh.n : sh.n_out;
+    g.s = sh.s; g.p = sh.p; g.k = sh.k;
+    g.tr = tr ? 1 : 0;
     g.batch = batch;
     g.nnz = (int)plan->nnz;
-    const int64_t iw = (int64_t)(tw - 1) * sh.s + sh.k;
+    // operand columns a strip of tw result columns can touch, operand lines in use or arriving
+    // during a step of 2 (1) result lines, and new operand lines per step -- upper bounds
+    const int64_t iw = tr ? (int64_t)(tw - 2 + sh.k) / sh.s + 2 : (int64_t)(tw - 1) * sh.s + sh.k;
+    const int64_t need2 = tr ? (int64_t)(sh.k + 2) / sh.s + 2 : (int64_t)sh.s * 3 + sh.k;
+    const int64_t need1 = tr ? (int64_t)sh.k / sh.s + 2 : (int64_t)sh.s + sh.k;
+    const int64_t new2 = tr ? 2 / sh.s + 1 : 2LL * sh.s, new1 = tr ? 1 / sh.s + 1 : sh.s;
     const int plane = march_plane(nv);
     if (iw + 16 > plane) return false;
     g.iw = (int)iw;
     g.iw_pitch = round_up_mod((int)iw, 16, 8);
-    // Ring of 16 lines with steps of two output lines when the ring (s*3 + k lines in
-    // use or arriving), the LDS plane and the per-thread line registers (2 per thread)
-    // allow it; else steps of one line (s + k lines, 2 registers) with 16 or 8 ring lines.
+    // Ring of 16 lines with steps of two result lines when the ring, the LDS plane and the
+    // per-thread line registers (2 per thread) allow it; else steps of one line with 16 or 8
+    // ring lines.
     const int threads = kMarchThreads, planes = nv ? nv : 1;
-    const bool regs1 = (int64_t)sh.s * iw * planes <= 2LL * threads;
+    auto regs = [&](int64_t lines) { return lines * iw * planes <= 2LL * threads; };
     auto fits = [&](int nl) { return (int64_t)nl * g.iw_pitch + 1 <= plane; };
     int ls = 0, nl = 0;
-    if ((int64_t)sh.s * 3 + sh.k <= 16 && 2LL * sh.s * iw * planes <= 2LL * threads && fits(16)) { ls = 2; nl = 16; }
-    else if ((int64_t)sh.s + sh.k <= 16 && regs1 && fits(16)) { ls = 1; nl = 16; }
-    else if ((int64_t)sh.s + sh.k <= 8 && regs1 && fits(8)) { ls = 1; nl = 8; }
+    if (need2 <= 16 && regs(new2) && fits(16)) { ls = 2; nl = 16; }
+    else if (need1 <= 16 && regs(new1) && fits(16)) { ls = 1; nl = 16; }
+    else if (need1 <= 8 && regs(new1) && fits(8)) { ls = 1; nl = 8; }
     if (ls == 0) return false;
     // int arithmetic in the kernel: s*x - p + k, col*16, d16 < 2^25 (see the kernel)
     if ((int64_t)sh.m + 2LL * sh.p + sh.k >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + iw >= (1LL << 30)) return false;
-    if (plan->cols > (1LL << 27) || 2LL * 16 * sh.n * 16 > (1LL << 25)) return false;
-    if (sh.n_out < tw / 2) return false;                // a strip would be mostly empty
-    g.strips = (sh.n_out + tw - 1) / tw;
+    if ((int64_t)g.m * g.n > (1LL << 27) || 2LL * 16 * g.n * 16 > (1LL << 25)) return false;
+    if (g.n_out < tw / 2) return false;                 // a strip would be mostly empty
+    g.strips = (g.n_out + tw - 1) / tw;
     const int col_blocks = nv ? batch / (4 * nv) : batch;
-    if ((int64_t)g.strips * ((sh.m_out + 7) / 8) * col_blocks < g_march_min_jobs.load(std::memory_order_relaxed)) return false;
+    if ((int64_t)g.strips * ((g.m_out + 7) / 8) * col_blocks < g_march_min_jobs.load(std::memory_order_relaxed)) return false;
     int64_t segs = kMarchTargetBlocks / ((int64_t)g.strips * col_blocks);
     if (segs < 1) segs = 1;
-    int64_t seg = (sh.m_out + segs - 1) / segs;
+    int64_t seg = (g.m_out + segs - 1) / segs;
     if (seg < 8) seg = 8;
     seg = (seg + 1) & ~1LL;
     g.seg = (int)seg;
-    g.segs = (int)((sh.m_out + seg - 1) / seg);
+    g.segs = (int)((g.m_out + seg - 1) / seg);
     const int64_t jobs = (int64_t)g.strips * g.segs;
     if (jobs + kXcds >= (1LL << 31) / kXcds) return false;
     g.blocks_per_xcd = (int)((jobs + kXcds - 1) / kXcds);
-    g.inv_n = 1.0f / (float)sh.n;
+    g.inv_n = 1.0f / (float)g.n;
     *out = g;
     *ls_out = ls;
     *nl_out = nl;
@@ -343,7 +355,6 @@ ApplyChoice choose_apply(const conv_plan *plan, const float *x, const float *y, 
     c.nv = !vec ? 0 : (batch % 16 == 0 ? 4 : (batch % 8 == 0 ? 2 : 1));
     c.kind = vec ? Kind::GatherVec : Kind::GatherScalar;
     if (plan->nnz == 0 || (!vec && batch != 1) || (vec && batch / (4 * c.nv) > 65535)) return c;
-    if (plan->transposed) return c;      // the staged kernels are laid out for T; T^T takes the row-group kernels
 
     // marching kernel: float4 column chunks, or one scalar column for a single vector (SpMV)
     MarchShape ms;
@@ -361,7 +372,7 @@ ApplyChoice choose_apply(const conv_plan *plan, const float *x, const float *y, 
         c.march = mg;
         return c;
     }
-    if (!vec) return c;
+    if (!vec || plan->transposed) return c;     // the tile kernel is laid out for T only
 
     // one LDS tile per workgroup when the rows fit its unrolled trip count and the
     // input window of at least one output line fits the LDS planes

@@ -114,3 +114,73 @@ def test_transposed_update_kernel_and_fused_apply():
     assert np.all(np.abs(z.cpu().numpy().astype(np.float64) - ref) <= 1e-5 * np.maximum(scale, 1e-30))
     multi.close()
     plan.close()
+
+
+# ---- the same with the marching kernel forced wherever its geometry allows
+
+@pytest.fixture
+def march_everywhere():
+    prev = cs.conv_set_march_min_jobs(1)
+    yield
+    cs.conv_set_march_min_jobs(prev)
+
+
+def test_transposed_march_exhaustive_tiny_grid(march_everywhere):
+    batches = itertools.cycle([1, 4, 8, 16])
+    count = 0
+    for shape in itertools.product(range(1, 6), range(1, 6), range(1, 5), range(1, 4), range(0, 5)):
+        m, n, k, s, p = shape
+        if k > m + 2 * p or k > n + 2 * p:
+            continue
+        batch = next(batches)
+        u, K = _rand_t(shape, batch, 2000 + count)
+        plan = build_plan_t(shape, K)
+        check_apply_t(plan, shape, K, u, batch)
+        plan.close()
+        count += 1
+    assert count > 1000
+
+
+def test_transposed_march_ragged_shapes(march_everywhere):
+    cases = [((37, 53, 7, 1, 3), 16), ((130, 67, 7, 1, 3), 16), ((65, 129, 7, 1, 3), 1), ((100, 90, 5, 2, 2), 16),
+             ((100, 90, 5, 2, 2), 1), ((33, 200, 3, 1, 1), 32), ((70, 70, 1, 1, 0), 16), ((70, 70, 2, 2, 0), 8),
+             ((75, 75, 9, 3, 8), 4), ((75, 75, 9, 3, 8), 16), ((90, 141, 11, 4, 5), 4), ((150, 150, 11, 1, 5), 8),
+             ((140, 40, 7, 3, 3), 16), ((40, 140, 7, 5, 0), 4), ((200, 200, 3, 2, 1), 16), ((120, 120, 9, 1, 4), 16),
+             ((50, 50, 2, 1, 5), 8), ((64, 64, 4, 1, 6), 1), ((97, 33, 6, 1, 2), 12), ((257, 300, 3, 1, 1), 4)]
+    variants = {}
+    for shape, batch in cases:
+        u, K = _rand_t(shape, batch, 19)
+        plan = build_plan_t(shape, K)
+        variants[(shape, batch)] = plan.variant(batch)
+        check_apply_t(plan, shape, K, u, batch)
+        plan.close()
+    marching = [v for v in variants.values() if v.startswith("lds_march")]
+    print(variants)
+    assert len(marching) >= 15, variants
+
+
+def test_transposed_march_reads_the_stored_arrays(march_everywhere):
+    shape, batch = (96, 80, 7, 1, 3), 16
+    m, n, k, s, p = shape
+    u, K = _rand_t(shape, batch, 23)
+    plan = build_plan_t(shape, K)
+    assert plan.variant(batch).startswith("lds_march")
+    ud = torch.from_numpy(u).to(device())
+    z0 = cs.conv_spmv(plan, ud, batch=batch).clone()
+    cp, ri, va = oracle.csc(m, n, k, s, p, K)
+    row = 40 * n + 9
+    e = int(cp[row]) + 5
+    new_col = plan.cols - 1
+    plan.col_idx[e] = new_col
+    z1 = cs.conv_spmv(plan, ud, batch=batch)
+    torch.cuda.synchronize()
+    z0h, z1h = z0.cpu().numpy().reshape(-1, batch), z1.cpu().numpy().reshape(-1, batch)
+    assert np.where(np.any(z0h != z1h, axis=1))[0].tolist() == [row]
+    U = u.reshape(-1, batch).astype(np.float64)
+    ri2 = ri.copy()
+    ri2[e] = new_col
+    seg = slice(int(cp[row]), int(cp[row + 1]))
+    want = (va[seg].astype(np.float64)[:, None] * U[ri2[seg]]).sum(axis=0)
+    scale = (np.abs(va[seg]).astype(np.float64)[:, None] * np.abs(U[ri2[seg]])).sum(axis=0)
+    assert np.all(np.abs(z1h[row] - want) <= 1e-5 * scale)
+    plan.close()
