@@ -277,6 +277,9 @@ std::atomic<int> g_march_min_jobs{256};
 
 struct MarchShape { int g, nit, tw; };
 bool march_shape(int max_row_nnz, MarchShape *out) {
+    // rows of fewer than 16 entries leave most of a group's lanes idle and the fixed cost
+    // of a pass (bounds, combine, store) unpaid: measured slower than the row-group kernels
+    if (max_row_nnz < 16) return false;
     if (max_row_nnz <= 16) *out = MarchShape{8, 2, 64};
     else if (max_row_nnz <= 32) *out = MarchShape{8, 4, 64};
     else if (max_row_nnz <= 56) *out = MarchShape{8, 7, 64};

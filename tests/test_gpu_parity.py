@@ -240,9 +240,9 @@ def test_march_ragged_shapes(march_everywhere):
         plan.close()
     marching = [v for v in variants.values() if v.startswith("lds_march")]
     print(variants)
-    assert len(marching) >= 22, variants
+    assert len(marching) >= 16, variants
     kinds = {v.split("_", 3)[3] for v in marching}          # ring/step/lanes/trip/columns
-    assert len(kinds) >= 10, kinds
+    assert len(kinds) >= 8, kinds
 
 
 @pytest.mark.parametrize("shape", sorted(set(workloads.densenet121_layer_shapes())))
