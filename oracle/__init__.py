@@ -58,6 +58,10 @@ def _load():
             lib.oracle_csc.restype = i64
             lib.oracle_conv_t.argtypes = [i] * 6 + [vp, vp, vp, vp]
             lib.oracle_conv_t.restype = i
+            lib.oracle_compact_rows.argtypes = [i] * 5 + [vp]
+            lib.oracle_compact_rows.restype = i64
+            lib.oracle_compact_decode.argtypes = [i, i, i64, vp, vp, vp, vp, vp, i64]
+            lib.oracle_compact_decode.restype = i64
             _lib = lib
     return _lib
 
@@ -166,3 +170,33 @@ def conv_t(m, n, k, s, p, U, K, batch: int = 1, want_scale: bool = False):
     if rc != 0:
         raise ValueError("oracle_conv_t failed (%d)" % rc)
     return (out, scale) if want_scale else out
+
+
+def compact_rows(m, n, k, s, p):
+    """Per-row descriptors of the structure-aware storage of T: int32 (rows, 2), column 0 the
+    column index of the row's first entry, column 1 the packed tap ranges
+    a_lo | r1 << 8 | b_lo << 16 | r2 << 24 (bit pattern); both 0 for a row without entries."""
+    mo, no = out_shape(m, n, k, s, p)
+    desc = np.empty((mo * no, 2), dtype=np.int32)
+    rc = int(_load().oracle_compact_rows(m, n, k, s, p, desc.ctypes.data))
+    if rc < 0:
+        raise ValueError("oracle_compact_rows failed (%d)" % rc)
+    return desc
+
+
+def compact_decode(n, k, desc, ktab):
+    """CSR (row_ptr, col_idx int64, vals float32) of the matrix that descriptors + value table
+    stand for; the descriptors are taken as they are."""
+    desc = np.ascontiguousarray(desc, dtype=np.int32).reshape(-1, 2)
+    ktab = _f32(ktab).reshape(k * k)
+    rows = desc.shape[0]
+    cap = max(rows * k * k, 1)
+    row_ptr = np.empty(rows + 1, dtype=np.int64)
+    col_idx = np.empty(cap, dtype=np.int64)
+    vals = np.empty(cap, dtype=np.float32)
+    nnz = int(_load().oracle_compact_decode(n, k, rows, desc.ctypes.data, ktab.ctypes.data,
+                                            row_ptr.ctypes.data, col_idx.ctypes.data,
+                                            vals.ctypes.data, cap))
+    if nnz < 0:
+        raise ValueError("oracle_compact_decode failed (%d)" % nnz)
+    return row_ptr, col_idx[:nnz].copy(), vals[:nnz].copy()

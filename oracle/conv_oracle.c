@@ -276,3 +276,77 @@ int oracle_conv_t(int m, int n, int k, int s, int p, int B,
     }
     return fail ? -2 : 0;
 }
+
+/* ---- structure-aware storage of T (the "more efficient sparse representation"
+ * the paper leaves to future work, Sections 4.2 and 5) ------------------------
+ *
+ * Every value of T is one of the k*k kernel numbers, and the entries of row
+ * (x, y) are the taps a in [a_lo, a_lo + r1), b in [b_lo, b_lo + r2) that land
+ * on A (Theorem 2.1: r1 = k - c1(x), r2 = k - c2(y)), at columns
+ * base + da*n + db with base the column of the first one.  The compact storage
+ * keeps, per row, the pair
+ *     desc[2r]     = base                     (0 for a row without entries)
+ *     desc[2r + 1] = a_lo | r1 << 8 | b_lo << 16 | r2 << 24   (0 likewise)
+ * and once the table ktab[a*k + b] = K[a][b].  It needs k <= 255.
+ *
+ * oracle_compact_rows finds the ranges by testing every tap against the border,
+ * the same test oracle_csr_row makes.  Returns the number of rows, < 0 on error. */
+int64_t oracle_compact_rows(int m, int n, int k, int s, int p, int32_t *desc)
+{
+    int64_t mo, no;
+    if (oracle_out_shape(m, n, k, s, p, &mo, &no) != 0) return -1;
+    if (k > 255) return -1;
+    for (int64_t x = 0; x < mo; ++x)
+        for (int64_t y = 0; y < no; ++y) {
+            int64_t a_lo = -1, r1 = 0, b_lo = -1, r2 = 0;
+            for (int64_t a = 0; a < k; ++a) {
+                int64_t ip = s * x + a;
+                if (ip < p || ip >= p + m) continue;
+                if (a_lo < 0) a_lo = a;
+                ++r1;
+            }
+            for (int64_t b = 0; b < k; ++b) {
+                int64_t jp = s * y + b;
+                if (jp < p || jp >= p + n) continue;
+                if (b_lo < 0) b_lo = b;
+                ++r2;
+            }
+            int64_t r = x * no + y;
+            if (r1 == 0 || r2 == 0) {
+                desc[2 * r] = 0;
+                desc[2 * r + 1] = 0;
+            } else {
+                uint32_t w = (uint32_t)a_lo | (uint32_t)r1 << 8 | (uint32_t)b_lo << 16 | (uint32_t)r2 << 24;
+                desc[2 * r] = (int32_t)((s * x + a_lo - p) * n + (s * y + b_lo - p));
+                memcpy(&desc[2 * r + 1], &w, sizeof w);
+            }
+        }
+    return mo * no;
+}
+
+/* The matrix a compact storage stands for, in CSR: row r holds, for da < r1 and
+ * db < r2 in that order, column base + da*n + db with value
+ * ktab[(a_lo + da)*k + b_lo + db].  Works on whatever desc holds (it need not come
+ * from oracle_compact_rows).  Returns nnz, -3 if cap is too small, -4 if a tap
+ * index leaves the table. */
+int64_t oracle_compact_decode(int n, int k, int64_t rows, const int32_t *desc, const float *ktab,
+                              int64_t *row_ptr, int64_t *col_idx, float *vals, int64_t cap)
+{
+    int64_t at = 0;
+    for (int64_t r = 0; r < rows; ++r) {
+        uint32_t w;
+        memcpy(&w, &desc[2 * r + 1], sizeof w);
+        int64_t a_lo = w & 255u, r1 = (w >> 8) & 255u, b_lo = (w >> 16) & 255u, r2 = w >> 24;
+        row_ptr[r] = at;
+        if (a_lo + r1 > k || b_lo + r2 > k) return -4;
+        for (int64_t da = 0; da < r1; ++da)
+            for (int64_t db = 0; db < r2; ++db) {
+                if (at >= cap) return -3;
+                col_idx[at] = (int64_t)desc[2 * r] + da * n + db;
+                vals[at] = ktab[(a_lo + da) * k + (b_lo + db)];
+                ++at;
+            }
+    }
+    row_ptr[rows] = at;
+    return at;
+}
