@@ -93,6 +93,31 @@ int conv_csc_build(int m, int n, int k, int s, int p,
                    int32_t *col_ptr_dev, int32_t *row_idx_dev, float *vals_dev,
                    void *stream, conv_plan **plan_out);
 
+/* Build T in a structure-aware storage (the paper's closing remarks, Sections
+ * 4.2 and 5, point at formats that use the block structure of C).  By
+ * Section 2 and Theorem 2.1 the entries of row (x, y) are the r1 x r2
+ * rectangle of taps a in [a_lo, a_lo + r1), b in [b_lo, b_lo + r2) with
+ * a_lo = max(0, p - s x), r1 = k - c1(x) (b_lo, r2 likewise along n), and all
+ * their values come from the k*k kernel.  So T is stored as
+ *   row_desc_dev : 2*m_out*n_out int32, device, 8-byte aligned, written: for row
+ *                  r the pair { base, a_lo | r1 << 8 | b_lo << 16 | r2 << 24 },
+ *                  base = column of the row's first entry; {0, 0} for a row
+ *                  without entries;
+ *   ktab_dev     : k*k fp32, device, written: a copy of K, row-major.
+ * Entry (da, db) of row r, da < r1, db < r2, is column base + da*n + db with
+ * value ktab[(a_lo + da)*k + b_lo + db].  That is 8 bytes per row plus 4*k*k
+ * instead of 8 bytes per entry.  Needs k <= 255 (CONV_EINVAL otherwise).
+ * Both arrays are allocated by the caller and BORROWED by the plan.  conv_spmv
+ * on the plan computes y = T x from these arrays as they are stored: the result
+ * is the product with whatever matrix they describe, provided a_lo + r1 <= k,
+ * b_lo + r2 <= k and every described column lies in [0, m*n).
+ * conv_update_kernel rewrites ktab only (k*k numbers); conv_multi_create does
+ * not accept such a plan.  On error nothing is enqueued and *plan_out is NULL. */
+int conv_compact_build(int m, int n, int k, int s, int p,
+                       const float *kernel_dev,
+                       int32_t *row_desc_dev, float *ktab_dev,
+                       void *stream, conv_plan **plan_out);
+
 /* Replace the kernel of a built T: rewrites the plan's vals array from a new
  * K of the same size (k*k fp32, row-major, device); row_ptr and col_idx do not
  * depend on K and are left alone.  The paper notes (Section 4.2) that the
@@ -116,11 +141,12 @@ int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream);
 int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch, void *stream);
 
 /* Shape and size queries on a plan (host only).  conv_plan_is_transposed
- * returns 1 for a plan made by conv_csc_build, 0 for conv_csr_build, < 0 on
- * error. */
+ * returns 1 for a plan made by conv_csc_build, conv_plan_is_compact 1 for a
+ * plan made by conv_compact_build, 0 otherwise, < 0 on error. */
 int conv_plan_shape(const conv_plan *plan, int *m, int *n, int *k, int *s, int *p,
                     int *m_out, int *n_out, int64_t *nnz);
 int conv_plan_is_transposed(const conv_plan *plan);
+int conv_plan_is_compact(const conv_plan *plan);
 
 /* Name of the apply variant conv_spmv would launch for this batch with
  * 16-byte-aligned x and y (for reports), or NULL on bad arguments.  The text

@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     ConvMulti,
     ConvPlan,
     conv_csc_build,
+    conv_compact_build,
     conv_csr_build,
     conv_nnz,
     conv_out_shape,

@@ -22,6 +22,7 @@ EXPORTS = (
     "conv_set_march_min_jobs", "conv_update_kernel",
     "conv_multi_create", "conv_multi_apply", "conv_multi_destroy",
     "conv_csc_build", "conv_plan_is_transposed",
+    "conv_compact_build", "conv_plan_is_compact",
 )
 
 
@@ -58,6 +59,10 @@ def _load():
         lib.conv_csc_build.restype = i
         lib.conv_plan_is_transposed.argtypes = [vp]
         lib.conv_plan_is_transposed.restype = i
+        lib.conv_compact_build.argtypes = [i, i, i, i, i, vp, vp, vp, vp, ctypes.POINTER(vp)]
+        lib.conv_compact_build.restype = i
+        lib.conv_plan_is_compact.argtypes = [vp]
+        lib.conv_plan_is_compact.restype = i
         lib.conv_spmv.argtypes = [vp, vp, vp, i, vp]
         lib.conv_spmv.restype = i
         lib.conv_plan_shape.argtypes = [vp, pi, pi, pi, pi, pi, pi, pi, pi64]
@@ -131,6 +136,8 @@ class ConvPlan:
         self.nnz = nnz
         self.row_ptr, self.col_idx, self.vals = row_ptr, col_idx, vals
         self._kernel = kernel           # keep K alive until the build has run
+        self.compact = False
+        self.row_desc = self.ktab = None   # structure-aware storage (conv_compact_build)
 
     @property
     def rows(self):
@@ -147,6 +154,8 @@ class ConvPlan:
     def model_bytes(self, batch: int) -> int:
         """Bytes a CSR SpMM has to move: entries (index + value), row_ptr,
         x once, y once."""
+        if self.compact:    # descriptors and the value table instead of the entries
+            return self.rows * 8 + self.k * self.k * 4 + self.cols * batch * 4 + self.rows * batch * 4
         return self.nnz * 8 + (self.rows + 1) * 4 + self.cols * batch * 4 + self.rows * batch * 4
 
     def close(self):
@@ -192,6 +201,34 @@ def conv_csr_build(m, n, k, s, p, kernel, stream=None, _transposed=False) -> Con
     if st != 0:
         raise ConvError(st, "%s%r" % ("conv_csc_build" if _transposed else "conv_csr_build", (m, n, k, s, p)))
     return ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, row_ptr, col_idx, vals, kernel, transposed=_transposed)
+
+
+def conv_compact_build(m, n, k, s, p, kernel, stream=None) -> ConvPlan:
+    """Build T in the structure-aware storage: plan.row_desc is int32 (rows, 2) = per row the
+    column of its first entry and the packed tap ranges, plan.ktab the k*k value table."""
+    import torch
+    lib = _load()
+    mo, no = conv_out_shape(m, n, k, s, p)
+    nnz = conv_nnz(m, n, k, s, p)
+    if not (kernel.is_cuda and kernel.dtype == torch.float32 and kernel.is_contiguous()
+            and kernel.numel() == k * k):
+        raise ValueError("kernel must be a contiguous float32 device tensor with k*k elements")
+    dev = kernel.device
+    if mo * no >= 2 ** 31 - 1 or m * n >= 2 ** 31 - 1:
+        raise ConvError(-3, "conv_compact_build%r" % ((m, n, k, s, p),))
+    row_desc = torch.empty((mo * no, 2), dtype=torch.int32, device=dev)
+    ktab = torch.empty(k * k, dtype=torch.float32, device=dev)
+    handle = ctypes.c_void_p()
+    with torch.cuda.device(dev):
+        sh, _ = _stream_handle(stream)
+        st = lib.conv_compact_build(m, n, k, s, p, kernel.data_ptr(), row_desc.data_ptr(), ktab.data_ptr(), sh,
+                                    ctypes.byref(handle))
+    if st != 0:
+        raise ConvError(st, "conv_compact_build%r" % ((m, n, k, s, p),))
+    plan = ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, None, None, None, kernel)
+    plan.compact = True
+    plan.row_desc, plan.ktab = row_desc, ktab
+    return plan
 
 
 def conv_update_kernel(plan: ConvPlan, kernel, stream=None) -> None:

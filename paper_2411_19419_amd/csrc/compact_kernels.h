@@ -1,0 +1,319 @@
+// Structure-aware storage of T and its product (gfx950).
+//
+// The paper closes (Sections 4.2 and 5) by pointing at sparse formats that use the
+// block structure of C.  That structure, spelled out by Section 2 and Theorem 2.1:
+// every value of T is one of the k*k kernel numbers, and the entries of row (x, y)
+// are the r1(x) x r2(y) rectangle of taps that starts at (a_lo, b_lo) =
+// (max(0, p - s x), max(0, p - s y)), at columns base + da*n + db, base being the
+// column of the first one.  So T is stored as
+//   desc[r] = { base, a_lo | r1 << 8 | b_lo << 16 | r2 << 24 }   (8 bytes per row;
+//             {0, 0} for a row without entries)
+//   ktab[a*k + b] = K[a][b]                                       (k*k floats)
+// and entry (da, db) of row r is column base + da*n + db with value
+// ktab[(a_lo + da)*k + b_lo + db].  Per stored entry this is 8/(r1 r2) bytes
+// instead of 8.
+//
+// The product kernel keeps the marching layout of the CSR kernel (a workgroup
+// walks down a strip of output columns with the input lines it needs in a ring of
+// LDS lines) but has no entry stream to wait for, so the arithmetic decides its
+// speed.  Two paths:
+//   - the described path: every lane decodes the descriptor of its row and walks
+//     the rectangle it describes, whatever it is (borders, any k and s, edited
+//     descriptors; a tap whose column is not on a resident line is read from
+//     global memory);
+//   - for common (k, s), compiled in: when every row a wave holds is described as
+//     a full k x k rectangle at the position the stride dictates (checked on the
+//     descriptors read, not assumed), a lane computes RV vertically adjacent
+//     outputs at once, so that a pixel read from LDS feeds the taps of up to RV
+//     rows, with the kernel numbers in scalar registers and the LDS offsets of a
+//     line's pixels as immediates.
+#pragma once
+#include <type_traits>
+
+#include "apply_march_kernel.h"
+#include "build_kernels.h"
+
+namespace convspmv {
+
+// ---------------------------------------------------------------------------
+// Build: one thread per row
+// ---------------------------------------------------------------------------
+constexpr int kCompactBuildThreads = 256;
+
+__global__ __launch_bounds__(kCompactBuildThreads) void compact_rows_kernel(ConvShape sh, int2 *__restrict__ desc) {
+    const int blocks_per_line = (sh.n_out + kCompactBuildThreads - 1) / kCompactBuildThreads;
+    const int x = blockIdx.x / blocks_per_line;
+    const int y = (blockIdx.x - x * blocks_per_line) * kCompactBuildThreads + (int)threadIdx.x;
+    if (y >= sh.n_out) return;
+    const int r1 = axis_taps(x, sh.m, sh.k, sh.s, sh.p), r2 = axis_taps(y, sh.n, sh.k, sh.s, sh.p);
+    int2 d = make_int2(0, 0);
+    if (r1 > 0 && r2 > 0) {
+        // with r > 0 the first in-image tap is max(0, p - s t) < k
+        const long long sx = (long long)sh.s * x, sy = (long long)sh.s * y;
+        const int a_lo = sh.p > sx ? (int)(sh.p - sx) : 0, b_lo = sh.p > sy ? (int)(sh.p - sy) : 0;
+        d.x = (int)((sx + a_lo - sh.p) * sh.n + (sy + b_lo - sh.p));
+        d.y = (int)((unsigned)a_lo | (unsigned)r1 << 8 | (unsigned)b_lo << 16 | (unsigned)r2 << 24);
+    }
+    desc[(long long)x * sh.n_out + y] = d;
+}
+
+__global__ void compact_table_kernel(const float *__restrict__ kernel, float *__restrict__ ktab, int count) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < count) ktab[t] = kernel[t];
+}
+
+// ---------------------------------------------------------------------------
+// Product
+// ---------------------------------------------------------------------------
+struct CompactGeom {
+    int m, n, m_out, n_out, s, p, k;
+    int batch;            // x / y row pitch, in floats
+    int strips;           // strips of TW output columns
+    int seg;              // output lines per workgroup (a multiple of rv)
+    int segs;             // segments per strip
+    int blocks_per_xcd;
+    int iw;               // input pixels a strip can touch: (TW-1)*s + k; also the LDS pixels per ring line
+    int rv;               // output lines per step
+    int nl;               // ring lines (power of two); 0: no ring, every tap is read from global memory
+    int ktab_lds;         // 1: the table is copied to LDS behind the ring
+};
+
+constexpr int kCompactThreads = 256;
+
+// KK, SS: kernel size and stride the rectangle path is compiled for (0, 0: described
+// path only, k, s, rv, nl from the geometry).  LPR lanes share a row, each with 4
+// batch columns (SCALAR: one lane, one column).  RV output lines per lane and step,
+// NL ring lines, XLD registers per thread that carry the next step's input lines
+// (0: the lines are copied after the step instead, behind a barrier).
+template <int KK, int SS, int LPR, bool SCALAR, int RV, int NL, int XLD>
+__global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const int2 *__restrict__ desc,
+                                                                          const float *__restrict__ ktab,
+                                                                          const float *__restrict__ x,
+                                                                          float *__restrict__ y, CompactGeom g) {
+    using elem_t = typename std::conditional<SCALAR, float, vec4>::type;
+    constexpr int NT = kCompactThreads, TW = NT / LPR;
+    constexpr int NCOL = SCALAR ? 1 : 4 * LPR;
+    constexpr bool FAST = KK > 0;
+    static_assert(!SCALAR || LPR == 1, "scalar mode has one lane per row");
+    static_assert(FAST ? (SS > 0 && RV > 0 && NL > 0 && SS * (2 * RV - 1) + KK <= NL) : (SS == 0 && RV == 0 && NL == 0),
+                  "rectangle path needs compile-time geometry");
+    static_assert(NL == 0 || (NL & (NL - 1)) == 0, "ring lines");
+    extern __shared__ float4 smem[];
+    elem_t *xs = reinterpret_cast<elem_t *>(smem);
+
+    const int s = FAST ? SS : g.s, k = FAST ? KK : g.k;
+    const int rv = FAST ? RV : g.rv;
+    const bool ring = FAST || g.nl > 0;
+    const int nlm = FAST ? NL - 1 : g.nl - 1;
+    const int pitchE = g.iw * LPR;                 // elements per ring line
+    const float *ks = reinterpret_cast<const float *>(xs + (nlm + 1) * pitchE);
+
+    // ---- which strip segment (an XCD owns a band of output lines across all strips)
+    const int local = blockIdx.x / kXcds;
+    const int job = (blockIdx.x % kXcds) * g.blocks_per_xcd + local;
+    if (local >= g.blocks_per_xcd || job >= g.strips * g.segs) return;      // uniform over the block
+    const int sg = job / g.strips, tx = job - sg * g.strips;
+    const int y0 = tx * TW, xa = sg * g.seg, xb = min(xa + g.seg, g.m_out);
+    const int twc = min(TW, g.n_out - y0);
+    const int c0 = blockIdx.y * NCOL;
+    const int tid = threadIdx.x, yy = tid / LPR, v = tid % LPR;
+
+    // ---- input columns of the strip, clipped to the image
+    const int j_lo = s * y0 - g.p;
+    const int j0 = min(max(j_lo, 0), g.n - 1);
+    const int iwc = max(min(j_lo + g.iw, g.n) - j0, 0);
+    const int lineE = iwc * LPR;                   // elements per line that exist
+    const float inv_lineE = 1.0f / (float)max(lineE, 1);
+
+    auto line_lo = [&](int xo) { return min(max(s * xo - g.p, 0), g.m); };
+    auto line_hi = [&](int xo, int cnt) { return min(max(s * (xo + cnt - 1) - g.p + k, 0), g.m); };
+    auto hi_of = [&](int xo) { return line_hi(xo, min(rv, xb - xo)); };      // one past the last line of the step at xo
+
+    auto src_of = [&](int i, int q) {              // element q of the strip's part of input line i
+        const int dj = q / LPR, vv = q % LPR;
+        return reinterpret_cast<const elem_t *>(x + ((long long)i * g.n + (j0 + dj)) * g.batch + c0) + vv;
+    };
+    auto copy_lines = [&](int lo, int hi) {
+        const int items = (hi - lo) * lineE;
+        for (int item = tid; item < items; item += NT) {
+            const int dl = div_small(item, inv_lineE), q = item - dl * lineE;
+            xs[((lo + dl) & nlm) * pitchE + q] = *src_of(lo + dl, q);
+        }
+    };
+
+    // ---- next step's lines: global -> registers during the step, registers -> LDS at its end
+    constexpr int NX = XLD > 0 ? XLD : 1;
+    elem_t xr[NX];
+    int xdst[NX];
+    auto load_next = [&](int xo_next) {
+        int items = 0, lo = 0;
+        if (xo_next < xb) {
+            lo = max(line_hi(xo_next - rv, rv), line_lo(xo_next));
+            items = max(hi_of(xo_next) - lo, 0) * lineE;
+        }
+#pragma unroll
+        for (int r = 0; r < NX; ++r) {
+            const int item = tid + r * NT;
+            xdst[r] = -1;
+            if (item < items) {
+                const int dl = div_small(item, inv_lineE), q = item - dl * lineE;
+                xr[r] = *src_of(lo + dl, q);
+                xdst[r] = ((lo + dl) & nlm) * pitchE + q;
+            }
+        }
+    };
+    auto store_next = [&]() {
+#pragma unroll
+        for (int r = 0; r < NX; ++r)
+            if (xdst[r] >= 0) xs[xdst[r]] = xr[r];
+    };
+
+    auto fma_elem = [](elem_t &a, float wt, const elem_t &e) {
+        if constexpr (SCALAR) {
+            a = fmaf(wt, e, a);
+        } else {
+            a.x = fmaf(wt, e.x, a.x);
+            a.y = fmaf(wt, e.y, a.y);
+            a.z = fmaf(wt, e.z, a.z);
+            a.w = fmaf(wt, e.w, a.w);
+        }
+    };
+    auto store_y = [&](int xr_, const elem_t &a) {
+        elem_t *dst = reinterpret_cast<elem_t *>(y + ((long long)xr_ * g.n_out + (y0 + yy)) * g.batch + c0) + v;
+        __builtin_nontemporal_store(a, dst);
+    };
+
+    // ---- described path: one row, whatever its descriptor says
+    auto row_described = [&](int xr_, int2 d, int lo_step, int hi_step) {
+        const unsigned w = (unsigned)d.y;
+        const int a_lo = w & 255u, r1 = (w >> 8) & 255u, b_lo = (w >> 16) & 255u, r2 = w >> 24;
+        const int i_first = d.x / g.n, j_first = d.x - i_first * g.n;
+        elem_t acc = elem_t(0.0f);
+        for (int da = 0; da < r1; ++da) {
+            const int i = i_first + da;
+            const bool line_in = ring && i >= lo_step && i < hi_step;
+            const int kbase = (a_lo + da) * k + b_lo;
+            const int lbase = (i & nlm) * pitchE + (j_first - j0) * LPR + v;
+            for (int db = 0; db < r2; ++db) {
+                const float kv = g.ktab_lds ? ks[kbase + db] : ktab[kbase + db];
+                const int j = j_first + db;
+                elem_t e;
+                if (line_in && j >= j0 && j < j0 + iwc)
+                    e = xs[lbase + db * LPR];
+                else
+                    e = *(reinterpret_cast<const elem_t *>(x + ((long long)d.x + (long long)da * g.n + db) * g.batch + c0) + v);
+                fma_elem(acc, kv, e);
+            }
+        }
+        store_y(xr_, acc);
+    };
+
+    // ---- rectangle path state
+    constexpr int NK = FAST ? KK * KK : 1;
+    constexpr int NR = FAST ? RV : 1;
+    float kk[NK];
+    int2 d_cur[NR], d_nxt[NR];
+    auto load_desc = [&](int xo, int2 (&d)[NR]) {
+#pragma unroll
+        for (int j = 0; j < NR; ++j) {
+            const int xr_ = min(xo + j, g.m_out - 1), yr = y0 + min(yy, twc - 1);
+            d[j] = desc[(long long)xr_ * g.n_out + yr];
+        }
+    };
+
+    auto compute = [&](int xo) {
+        const int lo_step = line_lo(xo), hi_step = hi_of(xo);
+        if constexpr (FAST) {
+            constexpr int FULL = KK << 8 | KK << 24;
+            bool ok = true;
+#pragma unroll
+            for (int j = 0; j < RV; ++j) {
+                const bool present = xo + j < xb && yy < twc;
+                const int want = (SS * (xo + j) - g.p) * g.n + SS * (y0 + yy) - g.p;
+                ok = ok && (!present || (d_cur[j].y == FULL && d_cur[j].x == want));
+            }
+            if (__all(ok)) {
+                // Every present row of the wave is a full rectangle in the regular place, so the
+                // taps of output line xo + j are input lines SS*(xo+j) - p + a, all resident.
+                // Lanes without a row compute on clamped, in-bounds LDS addresses and store nothing.
+                const int i0 = SS * xo - g.p;
+                const int jj = min(max(SS * (y0 + yy) - g.p - j0, 0), g.iw - KK);
+                const elem_t *lane_base = xs + jj * LPR + v;
+                constexpr int LINES = (RV - 1) * SS + KK;
+                elem_t e[2][KK];
+                elem_t acc[RV];
+#pragma unroll
+                for (int j = 0; j < RV; ++j) acc[j] = elem_t(0.0f);
+                auto read_line = [&](int di, elem_t (&dst)[KK]) {
+                    const elem_t *src = lane_base + ((i0 + di) & (NL - 1)) * pitchE;
+#pragma unroll
+                    for (int b = 0; b < KK; ++b) dst[b] = src[b * LPR];
+                };
+                read_line(0, e[0]);
+#pragma unroll
+                for (int di = 0; di < LINES; ++di) {
+                    if (di + 1 < LINES) read_line(di + 1, e[(di + 1) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int j = 0; j < RV; ++j) {
+                        const int a = di - j * SS;
+                        if (a >= 0 && a < KK) {
+#pragma unroll
+                            for (int b = 0; b < KK; ++b) fma_elem(acc[j], kk[a * KK + b], e[di & 1][b]);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                // the stores below are conditional; without this the compiler sinks each row's
+                // multiply-adds into its branch, behind all the LDS reads
+#pragma unroll
+                for (int j = 0; j < RV; ++j) {
+                    if constexpr (SCALAR) asm volatile("" : "+v"(acc[j]));
+                    else asm volatile("" : "+v"(acc[j].x), "+v"(acc[j].y), "+v"(acc[j].z), "+v"(acc[j].w));
+                }
+#pragma unroll
+                for (int j = 0; j < RV; ++j)
+                    if (xo + j < xb && yy < twc) store_y(xo + j, acc[j]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < RV; ++j)
+                    if (xo + j < xb && yy < twc) row_described(xo + j, d_cur[j], lo_step, hi_step);
+            }
+        } else {
+            if (yy < twc)
+                for (int j = 0; j < rv && xo + j < xb; ++j)
+                    row_described(xo + j, desc[(long long)(xo + j) * g.n_out + (y0 + yy)], lo_step, hi_step);
+        }
+    };
+
+    // ---- the march
+    if (ring) copy_lines(line_lo(xa), hi_of(xa));
+    if (g.ktab_lds)
+        for (int t = tid; t < k * k; t += NT) const_cast<float *>(ks)[t] = ktab[t];
+    if constexpr (FAST) {
+#pragma unroll
+        for (int t = 0; t < NK; ++t)
+            kk[t] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, ktab[t])));
+        load_desc(xa, d_nxt);
+    }
+    __syncthreads();
+    for (int xo = xa; xo < xb; xo += rv) {
+        if constexpr (XLD > 0) load_next(xo + rv);
+        if constexpr (FAST) {
+#pragma unroll
+            for (int j = 0; j < NR; ++j) d_cur[j] = d_nxt[j];
+            load_desc(xo + rv, d_nxt);
+        }
+        compute(xo);
+        if constexpr (XLD > 0) {
+            store_next();
+            __syncthreads();
+        } else if (ring) {
+            __syncthreads();
+            if (xo + rv < xb) copy_lines(max(hi_of(xo), line_lo(xo + rv)), hi_of(xo + rv));
+            __syncthreads();
+        }
+    }
+}
+
+}  // namespace convspmv

@@ -12,6 +12,7 @@
 #include "apply_march_kernel.h"
 #include "apply_tile_kernel.h"
 #include "build_kernels.h"
+#include "compact_kernels.h"
 
 using namespace convspmv;
 
@@ -64,6 +65,9 @@ struct conv_plan {
     int *axis_tab;            // owned, device: the two per-axis prefix tables of the build
     int device;
     bool transposed;          // the arrays hold T^T (CSC of T): rows = m*n, cols = m_out*n_out
+    bool compact;             // structure-aware storage: desc and ktab instead of the CSR arrays
+    const int2 *desc;         // borrowed, device: one descriptor per row
+    float *ktab;              // borrowed, device: k*k values (rewritten by conv_update_kernel)
 };
 
 extern "C" {
@@ -132,6 +136,9 @@ int build_impl(int m, int n, int k, int s, int p, const float *kernel_dev, int32
     plan->axis_tab = nullptr;
     plan->device = 0;
     plan->transposed = TR;
+    plan->compact = false;
+    plan->desc = nullptr;
+    plan->ktab = nullptr;
     if (!hip_ok(hipGetDevice(&plan->device))) {
         delete plan;
         return CONV_EHIP;
@@ -169,8 +176,62 @@ int conv_csc_build(int m, int n, int k, int s, int p, const float *kernel_dev, i
     return build_impl<true>(m, n, k, s, p, kernel_dev, col_ptr_dev, row_idx_dev, vals_dev, stream, plan_out);
 }
 
+int conv_compact_build(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *row_desc_dev,
+                       float *ktab_dev, void *stream, conv_plan **plan_out) {
+    if (!plan_out) return CONV_ENULL;
+    *plan_out = nullptr;
+    int64_t mo, no;
+    int st = check_shape(m, n, k, s, p, &mo, &no);
+    if (st != CONV_OK) return st;
+    if (k > 255) return CONV_EINVAL;                       // tap ranges are stored in 8 bits
+    const int64_t nnz = conv_nnz(m, n, k, s, p);
+    if (nnz < 0) return (int)nnz;
+    const int64_t rows = mo * no, cols = (int64_t)m * n;
+    if (rows >= kInt32Limit || cols >= kInt32Limit || mo * (int64_t)k > kInt32Limit || no * (int64_t)k > kInt32Limit)
+        return CONV_EOVERFLOW;
+    const int64_t blocks = mo * ((no + kCompactBuildThreads - 1) / kCompactBuildThreads);
+    if (blocks > kInt32Limit) return CONV_EOVERFLOW;
+    if (!kernel_dev || !row_desc_dev || !ktab_dev) return CONV_ENULL;
+    if (((uintptr_t)row_desc_dev & 7u) != 0) return CONV_EINVAL;      // descriptors are read as 8-byte pairs
+
+    conv_plan *plan = new (std::nothrow) conv_plan;
+    if (!plan) return CONV_ENOMEM;
+    plan->shape = ConvShape{m, n, k, s, p, (int)mo, (int)no};
+    plan->rows = rows;
+    plan->cols = cols;
+    plan->nnz = nnz;
+    plan->max_row_nnz = k * k;
+    plan->row_ptr = nullptr;
+    plan->col_idx = nullptr;
+    plan->vals = nullptr;
+    plan->axis_tab = nullptr;
+    plan->device = 0;
+    plan->transposed = false;
+    plan->compact = true;
+    plan->desc = reinterpret_cast<const int2 *>(row_desc_dev);
+    plan->ktab = ktab_dev;
+    if (!hip_ok(hipGetDevice(&plan->device))) {
+        delete plan;
+        return CONV_EHIP;
+    }
+    hipStream_t q = (hipStream_t)stream;
+    compact_rows_kernel<<<(unsigned)blocks, kCompactBuildThreads, 0, q>>>(plan->shape, reinterpret_cast<int2 *>(row_desc_dev));
+    compact_table_kernel<<<(k * k + 255) / 256, 256, 0, q>>>(kernel_dev, ktab_dev, k * k);
+    if (!hip_ok(hipGetLastError())) {
+        delete plan;
+        return CONV_EHIP;
+    }
+    *plan_out = plan;
+    return CONV_OK;
+}
+
 int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream) {
     if (!plan || !kernel_dev) return CONV_ENULL;
+    if (plan->compact) {
+        const int kk = plan->shape.k * plan->shape.k;
+        compact_table_kernel<<<(kk + 255) / 256, 256, 0, (hipStream_t)stream>>>(kernel_dev, plan->ktab, kk);
+        return hip_ok(hipGetLastError()) ? CONV_OK : CONV_EHIP;
+    }
     if (plan->nnz == 0) return CONV_OK;
     const int64_t l1 = plan->transposed ? plan->shape.m : plan->shape.m_out;
     const int64_t l2 = plan->transposed ? plan->shape.n : plan->shape.n_out;
@@ -516,6 +577,120 @@ bool launch_march(const ApplyChoice &c, const conv_plan *plan, const float *x, f
     }
 }
 
+// ---------------------------------------------------------------------------
+// Structure-aware storage: dispatch
+// ---------------------------------------------------------------------------
+struct CompactChoice {
+    bool ok;
+    int kk, ss;           // rectangle path compiled for this (k, s); 0, 0: described path only
+    int lpr;              // lanes per row (4 batch columns each); scalar: 1 lane, 1 column
+    bool scalar;
+    size_t lds;
+    unsigned col_blocks;
+    CompactGeom geom;
+};
+
+// rectangle path instantiations: s = 1 and these k, RV = 4 lines per lane, ring of 16
+constexpr int kRectRv = 4, kRectNl = 16, kRectXld = 5;
+constexpr int kCompactTargetBlocks = 512;
+
+bool rect_compiled(int k, int s) { return s == 1 && (k == 3 || k == 5 || k == 7); }
+
+CompactChoice choose_compact(const conv_plan *plan, const float *x, const float *y, int batch) {
+    const ConvShape &sh = plan->shape;
+    CompactChoice c{};
+    const bool aligned = ((((uintptr_t)x) | ((uintptr_t)y)) & 15u) == 0;
+    c.scalar = !(aligned && batch % 4 == 0);
+    c.lpr = c.scalar ? 1 : (batch % 16 == 0 ? 4 : (batch % 8 == 0 ? 2 : 1));
+    const int ncol = c.scalar ? 1 : 4 * c.lpr, eb = c.scalar ? 4 : 16;
+    if (batch / ncol > 65535) return c;
+    c.col_blocks = (unsigned)(batch / ncol);
+    const int tw = kCompactThreads / c.lpr;
+    CompactGeom g{};
+    g.m = sh.m; g.n = sh.n; g.m_out = sh.m_out; g.n_out = sh.n_out; g.s = sh.s; g.p = sh.p; g.k = sh.k;
+    g.batch = batch;
+    // int arithmetic in the kernel: s*x - p + k, s*y0 - p + iw
+    const int64_t iw = (int64_t)(tw - 1) * sh.s + sh.k;
+    if ((int64_t)sh.m + 2LL * sh.p + sh.k >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + iw >= (1LL << 30)) return c;
+    g.iw = (int)iw;
+    const int kk_bytes = sh.k * sh.k * 4;
+    // the rectangle path compares descriptors with (s*x - p)*n + s*y - p in int, for x up to m_out + RV
+    if (rect_compiled(sh.k, sh.s) && ((int64_t)sh.m + sh.p + sh.k + (kRectRv + 1) * (int64_t)sh.s) * sh.n < kInt32Limit) {
+        c.kk = sh.k;
+        c.ss = sh.s;
+        g.rv = kRectRv;
+        g.nl = kRectNl;
+        g.ktab_lds = 1;
+        c.lds = (size_t)kRectNl * iw * c.lpr * eb + kk_bytes;
+    } else {
+        // described path: the most lines per step whose ring fits 64 KiB (two barriers per
+        // step, so the ring holds one step's lines), else one line per step in up to 144 KiB;
+        // none fits: every tap from global memory
+        g.ktab_lds = kk_bytes <= 16 * 1024;
+        g.rv = 1;
+        g.nl = 0;
+        c.lds = g.ktab_lds ? kk_bytes : 0;
+        const int rvs[4] = {4, 2, 1, 1};
+        for (int t = 0; t < 4; ++t) {
+            const int rv = rvs[t];
+            const int64_t limit = t < 3 ? 64 * 1024 : 144 * 1024;
+            const int64_t need = (int64_t)sh.s * (rv - 1) + sh.k;
+            int nl = 16;
+            while (nl < need && nl < 256) nl <<= 1;
+            const int64_t bytes = (int64_t)nl * iw * c.lpr * eb + (g.ktab_lds ? kk_bytes : 0);
+            if (nl < need || bytes > limit || (int64_t)nl * iw * c.lpr >= (1LL << 21)) continue;
+            g.rv = rv;
+            g.nl = nl;
+            c.lds = (size_t)bytes;
+            break;
+        }
+    }
+    g.strips = (sh.n_out + tw - 1) / tw;
+    int64_t segs = kCompactTargetBlocks / ((int64_t)g.strips * c.col_blocks);
+    if (segs < 1) segs = 1;
+    int64_t seg = (sh.m_out + segs - 1) / segs;
+    if (seg < 2 * g.rv) seg = 2 * g.rv;
+    seg = (seg + g.rv - 1) / g.rv * g.rv;
+    g.seg = (int)seg;
+    g.segs = (int)((sh.m_out + seg - 1) / seg);
+    const int64_t jobs = (int64_t)g.strips * g.segs;
+    if (jobs + kXcds >= (1LL << 31) / kXcds) return c;
+    g.blocks_per_xcd = (int)((jobs + kXcds - 1) / kXcds);
+    c.geom = g;
+    c.ok = true;
+    return c;
+}
+
+template <int KK, int SS, int LPR, bool SCALAR>
+bool launch_compact_inst(const CompactChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    constexpr bool FAST = KK > 0;
+    auto kern = spmm_compact_kernel<KK, SS, LPR, SCALAR, FAST ? kRectRv : 0, FAST ? kRectNl : 0, FAST ? kRectXld : 0>;
+    static thread_local bool allowed[64];
+    if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
+    const dim3 grid((unsigned)(c.geom.blocks_per_xcd * kXcds), c.col_blocks);
+    kern<<<grid, kCompactThreads, c.lds, q>>>(plan->desc, plan->ktab, x, y, c.geom);
+    return true;
+}
+
+template <int LPR, bool SCALAR>
+bool launch_compact_k(const CompactChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    switch (c.kk) {
+        case 3: return launch_compact_inst<3, 1, LPR, SCALAR>(c, plan, x, y, q);
+        case 5: return launch_compact_inst<5, 1, LPR, SCALAR>(c, plan, x, y, q);
+        case 7: return launch_compact_inst<7, 1, LPR, SCALAR>(c, plan, x, y, q);
+        default: return launch_compact_inst<0, 0, LPR, SCALAR>(c, plan, x, y, q);
+    }
+}
+
+bool launch_compact(const CompactChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    if (c.scalar) return launch_compact_k<1, true>(c, plan, x, y, q);
+    switch (c.lpr) {
+        case 1: return launch_compact_k<1, false>(c, plan, x, y, q);
+        case 2: return launch_compact_k<2, false>(c, plan, x, y, q);
+        default: return launch_compact_k<4, false>(c, plan, x, y, q);
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -529,6 +704,12 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
         if (xb < ye && yb < xe) return CONV_EALIAS;
     }
     hipStream_t q = (hipStream_t)stream;
+    if (plan->compact) {
+        const CompactChoice cc = choose_compact(plan, x_dev, y_dev, batch);
+        if (!cc.ok) return CONV_EOVERFLOW;
+        if (!launch_compact(cc, plan, x_dev, y_dev, q)) return CONV_EHIP;
+        return hip_ok(hipGetLastError()) ? CONV_OK : CONV_EHIP;
+    }
     const ApplyChoice c = choose_apply(plan, x_dev, y_dev, batch);
     if (c.kind == Kind::March) {
         if (!launch_march(c, plan, x_dev, y_dev, q)) return CONV_EHIP;
@@ -573,7 +754,7 @@ int conv_multi_create(int n, const conv_plan *const *plans, const float *const *
     for (int i = 0; i < n && status == CONV_OK; ++i) {
         const conv_plan *p = plans[i];
         if (!p || !x_dev[i] || !y_dev[i]) { status = CONV_ENULL; break; }
-        if (p->device != plans[0]->device) { status = CONV_EINVAL; break; }
+        if (p->device != plans[0]->device || p->compact) { status = CONV_EINVAL; break; }
         const char *xb = (const char *)x_dev[i], *xe = xb + sizeof(float) * (size_t)p->cols * batch;
         const char *yb = (const char *)y_dev[i], *ye = yb + sizeof(float) * (size_t)p->rows * batch;
         if (xb < ye && yb < xe) { status = CONV_EALIAS; break; }
@@ -650,10 +831,25 @@ int conv_plan_shape(const conv_plan *plan, int *m, int *n, int *k, int *s, int *
 }
 
 int conv_plan_is_transposed(const conv_plan *plan) { return plan ? (plan->transposed ? 1 : 0) : CONV_ENULL; }
+int conv_plan_is_compact(const conv_plan *plan) { return plan ? (plan->compact ? 1 : 0) : CONV_ENULL; }
 
 const char *conv_spmv_variant(const conv_plan *plan, int batch) {
     if (!plan || batch < 1) return nullptr;
     static thread_local char name[96];
+    if (plan->compact) {
+        const CompactChoice cc = choose_compact(plan, nullptr, nullptr, batch);
+        if (!cc.ok) return nullptr;
+        char cols[16];
+        if (cc.scalar) snprintf(cols, sizeof cols, "scalar");
+        else snprintf(cols, sizeof cols, "float4x%d", cc.lpr);
+        if (cc.kk)
+            snprintf(name, sizeof name, "compact_rect_k%ds%d_%dx%d_ring%d_rv%d_%s", cc.kk, cc.ss, cc.geom.seg,
+                     kCompactThreads / cc.lpr, cc.geom.nl, cc.geom.rv, cols);
+        else
+            snprintf(name, sizeof name, "compact_described_%dx%d_ring%d_rv%d_%s", cc.geom.seg, kCompactThreads / cc.lpr,
+                     cc.geom.nl, cc.geom.rv, cols);
+        return name;
+    }
     const ApplyChoice c = choose_apply(plan, nullptr, nullptr, batch);
     switch (c.kind) {
         case Kind::GatherScalar: snprintf(name, sizeof name, "gather_g%d_scalar", c.g); break;

@@ -90,3 +90,19 @@ def check_apply_t(plan, shape, K, u, batch):
     assert scaled <= REL_TOL, "max err/scale %.3e" % scaled
     assert normwise <= REL_TOL, "normwise error %.3e" % normwise
     return scaled, normwise
+
+
+def build_plan_c(shape, K):
+    m, n, k, s, p = shape
+    return cs.conv_compact_build(m, n, k, s, p, torch.from_numpy(np.ascontiguousarray(K, dtype=np.float32)).to(device()))
+
+
+def check_compact(plan, shape, K):
+    """Row descriptors and value table of the structure-aware storage, bit-exact against the oracle."""
+    m, n, k, s, p = shape
+    want = oracle.compact_rows(m, n, k, s, p)
+    assert plan.compact and plan.nnz == oracle.nnz_closed(m, n, k, s, p)
+    got = plan.row_desc.cpu().numpy()
+    assert got.dtype == np.int32 and got.shape == want.shape and np.array_equal(got, want), "descriptors differ"
+    tab = plan.ktab.cpu().numpy()
+    assert np.array_equal(tab.view(np.uint32), np.ascontiguousarray(K, dtype=np.float32).reshape(-1).view(np.uint32))
