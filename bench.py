@@ -194,6 +194,8 @@ def main():
     ap.add_argument("--batch", type=int, default=1, help="batch of the densenet121_sweep workload")
     ap.add_argument("--transposed", action="store_true",
                     help="build T column-compressed and time y = T^T x (the adjoint) instead")
+    ap.add_argument("--compact", action="store_true",
+                    help="build T in the structure-aware storage (row descriptors + k*k table) and time y = T x from it")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -225,7 +227,10 @@ def main():
     stream = torch.cuda.current_stream()
 
     # ---- build (row_ptr + fill kernels; allocation of the CSR arrays excluded from the event time)
-    plan = (cs.conv_csc_build if args.transposed else cs.conv_csr_build)(m, n, k, s, p, K)
+    if args.compact and args.transposed:
+        sys.exit("--compact stores T; it has no transposed variant")
+    build_py = cs.conv_compact_build if args.compact else (cs.conv_csc_build if args.transposed else cs.conv_csr_build)
+    plan = build_py(m, n, k, s, p, K)
     torch.cuda.synchronize()
     build_ms = []
     lib = cs.binding._load()
@@ -234,9 +239,13 @@ def main():
         h = ctypes.c_void_p()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(stream)
-        build_fn = lib.conv_csc_build if args.transposed else lib.conv_csr_build
-        st = build_fn(m, n, k, s, p, K.data_ptr(), plan.row_ptr.data_ptr(), plan.col_idx.data_ptr(),
-                      plan.vals.data_ptr(), ctypes.c_void_p(stream.cuda_stream), ctypes.byref(h))
+        if args.compact:
+            st = lib.conv_compact_build(m, n, k, s, p, K.data_ptr(), plan.row_desc.data_ptr(), plan.ktab.data_ptr(),
+                                        ctypes.c_void_p(stream.cuda_stream), ctypes.byref(h))
+        else:
+            build_fn = lib.conv_csc_build if args.transposed else lib.conv_csr_build
+            st = build_fn(m, n, k, s, p, K.data_ptr(), plan.row_ptr.data_ptr(), plan.col_idx.data_ptr(),
+                          plan.vals.data_ptr(), ctypes.c_void_p(stream.cuda_stream), ctypes.byref(h))
         e1.record(stream)
         torch.cuda.synchronize()
         assert st == 0
@@ -321,7 +330,8 @@ def main():
         "config": {"workload": w.name, "m": m, "n": n, "k": k, "s": s, "p": p, "batch": w.batch,
                    "nnz": plan.nnz, "rows": plan.rows, "cols": plan.cols,
                    "apply_variant": plan.variant(w.batch), "streams": n_streams,
-                   "matrix": "T^T (CSC of T)" if args.transposed else "T (CSR)"},
+                   "matrix": "T (row descriptors + k*k table)" if args.compact
+                   else ("T^T (CSC of T)" if args.transposed else "T (CSR)")},
         "pct_of_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
         "useful_mac_per_s": plan.nnz * w.batch / (ms_per_step * 1e-3),
         "model_bytes": model_bytes,

@@ -118,26 +118,26 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
     const int c0 = blockIdx.y * NCOL;
     const int tid = threadIdx.x, yy = tid / LPR, v = tid % LPR;
 
-    // ---- input columns of the strip, clipped to the image
+    // ---- the ring holds the zero-padded plane: line i (any sign) in slot i mod NL, pixels
+    // j_lo .. j_lo + iw - 1 of it, zeros wherever (i, j) is not a pixel of the image
     const int j_lo = s * y0 - g.p;
-    const int j0 = min(max(j_lo, 0), g.n - 1);
-    const int iwc = max(min(j_lo + g.iw, g.n) - j0, 0);
-    const int lineE = iwc * LPR;                   // elements per line that exist
-    const float inv_lineE = 1.0f / (float)max(lineE, 1);
+    const float inv_pitchE = 1.0f / (float)pitchE;
 
-    auto line_lo = [&](int xo) { return min(max(s * xo - g.p, 0), g.m); };
-    auto line_hi = [&](int xo, int cnt) { return min(max(s * (xo + cnt - 1) - g.p + k, 0), g.m); };
-    auto hi_of = [&](int xo) { return line_hi(xo, min(rv, xb - xo)); };      // one past the last line of the step at xo
+    auto first_line = [&](int xo) { return s * xo - g.p; };
+    auto end_line = [&](int xo) { return s * (xo + min(rv, xb - xo) - 1) - g.p + k; };   // of the step at xo
 
-    auto src_of = [&](int i, int q) {              // element q of the strip's part of input line i
-        const int dj = q / LPR, vv = q % LPR;
-        return reinterpret_cast<const elem_t *>(x + ((long long)i * g.n + (j0 + dj)) * g.batch + c0) + vv;
+    auto fetch = [&](int i, int q) {               // element q of ring line i
+        const int j = j_lo + q / LPR, vv = q % LPR;
+        elem_t e = elem_t(0.0f);
+        if (i >= 0 && i < g.m && j >= 0 && j < g.n)
+            e = *(reinterpret_cast<const elem_t *>(x + ((long long)i * g.n + j) * g.batch + c0) + vv);
+        return e;
     };
     auto copy_lines = [&](int lo, int hi) {
-        const int items = (hi - lo) * lineE;
+        const int items = (hi - lo) * pitchE;
         for (int item = tid; item < items; item += NT) {
-            const int dl = div_small(item, inv_lineE), q = item - dl * lineE;
-            xs[((lo + dl) & nlm) * pitchE + q] = *src_of(lo + dl, q);
+            const int dl = div_small(item, inv_pitchE), q = item - dl * pitchE;
+            xs[((lo + dl) & nlm) * pitchE + q] = fetch(lo + dl, q);
         }
     };
 
@@ -148,16 +148,16 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
     auto load_next = [&](int xo_next) {
         int items = 0, lo = 0;
         if (xo_next < xb) {
-            lo = max(line_hi(xo_next - rv, rv), line_lo(xo_next));
-            items = max(hi_of(xo_next) - lo, 0) * lineE;
+            lo = max(first_line(xo_next - 1) + k, first_line(xo_next));      // the step before was a full one
+            items = max(end_line(xo_next) - lo, 0) * pitchE;
         }
 #pragma unroll
         for (int r = 0; r < NX; ++r) {
             const int item = tid + r * NT;
             xdst[r] = -1;
             if (item < items) {
-                const int dl = div_small(item, inv_lineE), q = item - dl * lineE;
-                xr[r] = *src_of(lo + dl, q);
+                const int dl = div_small(item, inv_pitchE), q = item - dl * pitchE;
+                xr[r] = fetch(lo + dl, q);
                 xdst[r] = ((lo + dl) & nlm) * pitchE + q;
             }
         }
@@ -193,14 +193,14 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
             const int i = i_first + da;
             const bool line_in = ring && i >= lo_step && i < hi_step;
             const int kbase = (a_lo + da) * k + b_lo;
-            const int lbase = (i & nlm) * pitchE + (j_first - j0) * LPR + v;
+            const int lbase = (i & nlm) * pitchE + (j_first - j_lo) * LPR + v;
             for (int db = 0; db < r2; ++db) {
                 const float kv = g.ktab_lds ? ks[kbase + db] : ktab[kbase + db];
                 const int j = j_first + db;
                 elem_t e;
-                if (line_in && j >= j0 && j < j0 + iwc)
+                if (line_in && j >= j_lo && j < j_lo + g.iw && j < g.n)
                     e = xs[lbase + db * LPR];
-                else
+                else   // not on a resident line, or past the end of its line (the column then belongs to the next one)
                     e = *(reinterpret_cast<const elem_t *>(x + ((long long)d.x + (long long)da * g.n + db) * g.batch + c0) + v);
                 fma_elem(acc, kv, e);
             }
@@ -221,24 +221,36 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
         }
     };
 
+    // What Theorem 2.1 says the descriptor of this lane's rows must be, split into the part that
+    // depends on the output column (fixed for the lane) and the part that depends on the line.
+    const int yl = y0 + yy;
+    const int b_lo_e = max(g.p - s * yl, 0), r2_e = k - b_lo_e - max(s * yl + k - g.n - g.p, 0);
+    const int lane_word = b_lo_e << 16 | r2_e << 24, lane_col = s * yl + b_lo_e - g.p;
+    bool kfinite = true;
+
     auto compute = [&](int xo) {
-        const int lo_step = line_lo(xo), hi_step = hi_of(xo);
+        const int lo_step = first_line(xo), hi_step = end_line(xo);
         if constexpr (FAST) {
             constexpr int FULL = KK << 8 | KK << 24;
             bool ok = true;
 #pragma unroll
             for (int j = 0; j < RV; ++j) {
-                const bool present = xo + j < xb && yy < twc;
-                const int want = (SS * (xo + j) - g.p) * g.n + SS * (y0 + yy) - g.p;
-                ok = ok && (!present || (d_cur[j].y == FULL && d_cur[j].x == want));
+                const int xr_ = xo + j;
+                const bool present = xr_ < xb && yy < twc;
+                const int a_lo_e = max(g.p - SS * xr_, 0), r1_e = KK - a_lo_e - max(SS * xr_ + KK - g.m - g.p, 0);
+                const bool live = r1_e > 0 && r2_e > 0;
+                const int word_e = live ? (a_lo_e | r1_e << 8 | lane_word) : 0;
+                const int base_e = live ? (SS * xr_ + a_lo_e - g.p) * g.n + lane_col : 0;
+                ok = ok && (!present || (d_cur[j].y == word_e && d_cur[j].x == base_e && (kfinite || word_e == FULL)));
             }
             if (__all(ok)) {
-                // Every present row of the wave is a full rectangle in the regular place, so the
-                // taps of output line xo + j are input lines SS*(xo+j) - p + a, all resident.
-                // Lanes without a row compute on clamped, in-bounds LDS addresses and store nothing.
+                // Every row the wave holds is described exactly as the window at its position: the
+                // taps it stores are those that land on the image, and the ring holds zeros where
+                // the others would land, so the full k x k sum over the padded plane is the row's
+                // sum (all kernel numbers are finite, or no tap is missing).  Lanes without a row
+                // compute on in-bounds LDS addresses and store nothing.
                 const int i0 = SS * xo - g.p;
-                const int jj = min(max(SS * (y0 + yy) - g.p - j0, 0), g.iw - KK);
-                const elem_t *lane_base = xs + jj * LPR + v;
+                const elem_t *lane_base = xs + SS * yy * LPR + v;
                 constexpr int LINES = (RV - 1) * SS + KK;
                 elem_t e[2][KK];
                 elem_t acc[RV];
@@ -287,13 +299,15 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
     };
 
     // ---- the march
-    if (ring) copy_lines(line_lo(xa), hi_of(xa));
+    if (ring) copy_lines(first_line(xa), end_line(xa));
     if (g.ktab_lds)
         for (int t = tid; t < k * k; t += NT) const_cast<float *>(ks)[t] = ktab[t];
     if constexpr (FAST) {
 #pragma unroll
         for (int t = 0; t < NK; ++t)
             kk[t] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, ktab[t])));
+#pragma unroll
+        for (int t = 0; t < NK; ++t) kfinite = kfinite && __builtin_isfinite(kk[t]);
         load_desc(xa, d_nxt);
     }
     __syncthreads();
@@ -310,7 +324,7 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
             __syncthreads();
         } else if (ring) {
             __syncthreads();
-            if (xo + rv < xb) copy_lines(max(hi_of(xo), line_lo(xo + rv)), hi_of(xo + rv));
+            if (xo + rv < xb) copy_lines(max(end_line(xo), first_line(xo + rv)), end_line(xo + rv));
             __syncthreads();
         }
     }
