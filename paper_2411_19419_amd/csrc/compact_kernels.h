@@ -134,10 +134,24 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
         return e;
     };
     auto copy_lines = [&](int lo, int hi) {
+        // four loads in flight per thread before the first is written to LDS
         const int items = (hi - lo) * pitchE;
-        for (int item = tid; item < items; item += NT) {
-            const int dl = div_small(item, inv_pitchE), q = item - dl * pitchE;
-            xs[((lo + dl) & nlm) * pitchE + q] = fetch(lo + dl, q);
+        for (int first = tid; first < items; first += 4 * NT) {
+            elem_t e[4];
+            int dst[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int item = first + u * NT;
+                dst[u] = -1;
+                if (item < items) {
+                    const int dl = div_small(item, inv_pitchE), q = item - dl * pitchE;
+                    e[u] = fetch(lo + dl, q);
+                    dst[u] = ((lo + dl) & nlm) * pitchE + q;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (dst[u] >= 0) xs[dst[u]] = e[u];
         }
     };
 
@@ -305,9 +319,13 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
     if constexpr (FAST) {
 #pragma unroll
         for (int t = 0; t < NK; ++t)
-            kk[t] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, ktab[t])));
+            kk[t] = ktab[t];
 #pragma unroll
         for (int t = 0; t < NK; ++t) kfinite = kfinite && __builtin_isfinite(kk[t]);
+        // the k*k numbers stay in vector registers (there is room for them); as scalars they
+        // crowd out the loop's addresses and bounds, which then travel through lane spills
+#pragma unroll
+        for (int t = 0; t < NK; ++t) asm volatile("" : "+v"(kk[t]));
         load_desc(xa, d_nxt);
     }
     __syncthreads();
