@@ -105,7 +105,8 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
     const int rv = FAST ? RV : g.rv;
     const bool ring = FAST || g.nl > 0;
     const int nlm = FAST ? NL - 1 : g.nl - 1;
-    const int pitchE = g.iw * LPR;                 // elements per ring line
+    // elements per ring line; the host sets g.iw = (TW-1)*s + k, a constant of the rectangle kernels
+    const int pitchE = FAST ? ((TW - 1) * SS + KK) * LPR : g.iw * LPR;
     const float *ks = reinterpret_cast<const float *>(xs + (nlm + 1) * pitchE);
 
     // ---- which strip segment (an XCD owns a band of output lines across all strips)
@@ -133,14 +134,16 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
             e = *(reinterpret_cast<const elem_t *>(x + ((long long)i * g.n + j) * g.batch + c0) + vv);
         return e;
     };
+    // CU loads in flight per thread before the first is written to LDS; the rectangle kernels
+    // take the lines of their first step in one round
+    constexpr int CU = FAST ? (((RV - 1) * SS + KK) * ((TW - 1) * SS + KK) * LPR + NT - 1) / NT : 4;
     auto copy_lines = [&](int lo, int hi) {
-        // four loads in flight per thread before the first is written to LDS
         const int items = (hi - lo) * pitchE;
-        for (int first = tid; first < items; first += 4 * NT) {
-            elem_t e[4];
-            int dst[4];
+        for (int first = tid; first < items; first += CU * NT) {
+            elem_t e[CU];
+            int dst[CU];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < CU; ++u) {
                 const int item = first + u * NT;
                 dst[u] = -1;
                 if (item < items) {
@@ -150,36 +153,56 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
                 }
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < CU; ++u)
                 if (dst[u] >= 0) xs[dst[u]] = e[u];
         }
     };
 
-    // ---- next step's lines: global -> registers during the step, registers -> LDS at its end
+    // ---- next step's lines: global -> registers during the step, registers -> LDS at its end.
+    // Every thread always issues XLD loads (clamped addresses): with a fixed number of loads
+    // in flight the waits on older loads (the descriptors of the current step) can leave
+    // these outstanding; a load inside a branch would make every such wait a wait for all.
     constexpr int NX = XLD > 0 ? XLD : 1;
     elem_t xr[NX];
-    int xdst[NX];
+    int xdst[NX];                        // LDS element, -1: nothing to write, -2 - element: write zeros
+    // Addresses are a wave-uniform 64-bit base (first line of the batch of lines) plus a 32-bit
+    // byte offset per lane, built from per-thread constants with 24-bit multiplies; the host
+    // admits this kernel only when a line of x is shorter than 2^24 bytes.
+    const int row_bytes = g.n * g.batch * 4;
+    int x_q[NX], x_dl[NX], x_coloff[NX];
+    bool x_colok[NX];
+#pragma unroll
+    for (int r = 0; r < NX; ++r) {
+        const int item = tid + r * NT;
+        x_dl[r] = div_small(item, inv_pitchE);
+        x_q[r] = item - x_dl[r] * pitchE;
+        const int j = j_lo + x_q[r] / LPR, vv = x_q[r] % LPR, jc = min(max(j, 0), g.n - 1);
+        x_colok[r] = j == jc;
+        x_coloff[r] = jc * g.batch * 4 + vv * (int)sizeof(elem_t);
+    }
     auto load_next = [&](int xo_next) {
         int items = 0, lo = 0;
         if (xo_next < xb) {
             lo = max(first_line(xo_next - 1) + k, first_line(xo_next));      // the step before was a full one
             items = max(end_line(xo_next) - lo, 0) * pitchE;
         }
+        const int base_line = min(max(lo, 0), g.m - 1);
+        const char *base = reinterpret_cast<const char *>(x) + ((long long)base_line * g.n * g.batch + c0) * 4;
 #pragma unroll
         for (int r = 0; r < NX; ++r) {
-            const int item = tid + r * NT;
-            xdst[r] = -1;
-            if (item < items) {
-                const int dl = div_small(item, inv_pitchE), q = item - dl * pitchE;
-                xr[r] = fetch(lo + dl, q);
-                xdst[r] = ((lo + dl) & nlm) * pitchE + q;
-            }
+            const int i = lo + x_dl[r], ic = min(max(i, 0), g.m - 1);
+            const unsigned off = __umul24(ic - base_line, row_bytes) + x_coloff[r];
+            xr[r] = *reinterpret_cast<const elem_t *>(base + off);
+            const int slot = __umul24(i & nlm, pitchE) + x_q[r];
+            xdst[r] = tid + r * NT >= items ? -1 : ((i == ic && x_colok[r]) ? slot : -2 - slot);
         }
     };
     auto store_next = [&]() {
 #pragma unroll
-        for (int r = 0; r < NX; ++r)
+        for (int r = 0; r < NX; ++r) {
             if (xdst[r] >= 0) xs[xdst[r]] = xr[r];
+            else if (xdst[r] < -1) xs[-2 - xdst[r]] = elem_t(0.0f);
+        }
     };
 
     auto fma_elem = [](elem_t &a, float wt, const elem_t &e) {
@@ -192,9 +215,10 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
             a.w = fmaf(wt, e.w, a.w);
         }
     };
+    const unsigned y_lane_off = (unsigned)yy * g.batch * 4 + v * (unsigned)sizeof(elem_t);
     auto store_y = [&](int xr_, const elem_t &a) {
-        elem_t *dst = reinterpret_cast<elem_t *>(y + ((long long)xr_ * g.n_out + (y0 + yy)) * g.batch + c0) + v;
-        __builtin_nontemporal_store(a, dst);
+        char *base = reinterpret_cast<char *>(y) + (((long long)xr_ * g.n_out + y0) * g.batch + c0) * 4;
+        __builtin_nontemporal_store(a, reinterpret_cast<elem_t *>(base + y_lane_off));
     };
 
     // ---- described path: one row, whatever its descriptor says
@@ -227,11 +251,13 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
     constexpr int NR = FAST ? RV : 1;
     float kk[NK];
     int2 d_cur[NR], d_nxt[NR];
+    const unsigned d_lane_off = (unsigned)min(yy, twc - 1) * 8u;
     auto load_desc = [&](int xo, int2 (&d)[NR]) {
 #pragma unroll
         for (int j = 0; j < NR; ++j) {
-            const int xr_ = min(xo + j, g.m_out - 1), yr = y0 + min(yy, twc - 1);
-            d[j] = desc[(long long)xr_ * g.n_out + yr];
+            const int xr_ = min(xo + j, g.m_out - 1);
+            const char *base = reinterpret_cast<const char *>(desc) + ((long long)xr_ * g.n_out + y0) * 8;
+            d[j] = *reinterpret_cast<const int2 *>(base + d_lane_off);
         }
     };
 

@@ -615,7 +615,9 @@ CompactChoice choose_compact(const conv_plan *plan, const float *x, const float 
     g.iw = (int)iw;
     const int kk_bytes = sh.k * sh.k * 4;
     // the rectangle path compares descriptors with (s*x - p)*n + s*y - p in int, for x up to m_out + RV
-    if (rect_compiled(sh.k, sh.s) && ((int64_t)sh.m + sh.p + sh.k + (kRectRv + 1) * (int64_t)sh.s) * sh.n < kInt32Limit) {
+    // ... and addresses lanes by 32-bit offsets from a line's start: n*batch*4 < 2^24, TW*batch*4 < 2^32
+    if (rect_compiled(sh.k, sh.s) && ((int64_t)sh.m + sh.p + sh.k + (kRectRv + 1) * (int64_t)sh.s) * sh.n < kInt32Limit &&
+        (int64_t)sh.n * batch * 4 < (1LL << 24) && (int64_t)batch * 4 * (kCompactThreads + 1) < (1LL << 31)) {
         c.kk = sh.k;
         c.ss = sh.s;
         g.rv = kRectRv;
