@@ -227,20 +227,32 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
         const int a_lo = w & 255u, r1 = (w >> 8) & 255u, b_lo = (w >> 16) & 255u, r2 = w >> 24;
         const int i_first = d.x / g.n, j_first = d.x - i_first * g.n;
         elem_t acc = elem_t(0.0f);
-        for (int da = 0; da < r1; ++da) {
-            const int i = i_first + da;
-            const bool line_in = ring && i >= lo_step && i < hi_step;
-            const int kbase = (a_lo + da) * k + b_lo;
-            const int lbase = (i & nlm) * pitchE + (j_first - j_lo) * LPR + v;
-            for (int db = 0; db < r2; ++db) {
-                const float kv = g.ktab_lds ? ks[kbase + db] : ktab[kbase + db];
-                const int j = j_first + db;
-                elem_t e;
-                if (line_in && j >= j_lo && j < j_lo + g.iw && j < g.n)
-                    e = xs[lbase + db * LPR];
-                else   // not on a resident line, or past the end of its line (the column then belongs to the next one)
-                    e = *(reinterpret_cast<const elem_t *>(x + ((long long)d.x + (long long)da * g.n + db) * g.batch + c0) + v);
-                fma_elem(acc, kv, e);
+        if (ring && g.ktab_lds && i_first >= lo_step && i_first + r1 <= hi_step && j_first >= j_lo &&
+            j_first + r2 <= min(j_lo + g.iw, g.n)) {
+            // the whole rectangle is on resident lines and inside one image line: no per-tap tests
+            const float *kp = ks + a_lo * k + b_lo;
+            const int lcol = (j_first - j_lo) * LPR + v;
+            for (int da = 0; da < r1; ++da) {
+                const elem_t *lp = xs + __umul24((i_first + da) & nlm, pitchE) + lcol;
+                for (int db = 0; db < r2; ++db) fma_elem(acc, kp[db], lp[db * LPR]);
+                kp += k;
+            }
+        } else {
+            for (int da = 0; da < r1; ++da) {
+                const int i = i_first + da;
+                const bool line_in = ring && i >= lo_step && i < hi_step;
+                const int kbase = (a_lo + da) * k + b_lo;
+                const int lbase = (i & nlm) * pitchE + (j_first - j_lo) * LPR + v;
+                for (int db = 0; db < r2; ++db) {
+                    const float kv = g.ktab_lds ? ks[kbase + db] : ktab[kbase + db];
+                    const int j = j_first + db;
+                    elem_t e;
+                    if (line_in && j >= j_lo && j < j_lo + g.iw && j < g.n)
+                        e = xs[lbase + db * LPR];
+                    else   // not on a resident line, or past the end of its line (the column then belongs to the next one)
+                        e = *(reinterpret_cast<const elem_t *>(x + ((long long)d.x + (long long)da * g.n + db) * g.batch + c0) + v);
+                    fma_elem(acc, kv, e);
+                }
             }
         }
         store_y(xr_, acc);
