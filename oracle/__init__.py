@@ -62,6 +62,8 @@ def _load():
             lib.oracle_compact_rows.restype = i64
             lib.oracle_compact_decode.argtypes = [i, i, i64, vp, vp, vp, vp, vp, i64]
             lib.oracle_compact_decode.restype = i64
+            lib.oracle_conv_channels.argtypes = [i] * 7 + [vp, vp, vp, vp]
+            lib.oracle_conv_channels.restype = i
             _lib = lib
     return _lib
 
@@ -200,3 +202,21 @@ def compact_decode(n, k, desc, ktab):
     if nnz < 0:
         raise ValueError("oracle_compact_decode failed (%d)" % nnz)
     return row_ptr, col_idx[:nnz].copy(), vals[:nnz].copy()
+
+
+def conv_channels(m, n, k, s, p, A, K, channels, batch: int = 1, want_scale: bool = False):
+    """Sum over `channels` input planes of the padded, strided convolution of plane ch with
+    kernel ch.  A: (channels*m*n*batch,) planes one after the other, each batch-minor; K:
+    (channels*k*k,).  Returns out (m_out*n_out*batch,) float32 (and the sums of |K||A|)."""
+    A = _f32(A).reshape(-1)
+    K = _f32(K).reshape(-1)
+    if A.size != channels * m * n * batch or K.size != channels * k * k:
+        raise ValueError("operand sizes do not match %d channels" % channels)
+    mo, no = out_shape(m, n, k, s, p)
+    out = np.empty(mo * no * batch, dtype=np.float32)
+    scale = np.empty(mo * no * batch, dtype=np.float64) if want_scale else None
+    rc = _load().oracle_conv_channels(m, n, k, s, p, batch, channels, A.ctypes.data, K.ctypes.data,
+                                      out.ctypes.data, scale.ctypes.data if want_scale else None)
+    if rc != 0:
+        raise ValueError("oracle_conv_channels failed (%d)" % rc)
+    return (out, scale) if want_scale else out

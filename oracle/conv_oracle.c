@@ -350,3 +350,46 @@ int64_t oracle_compact_decode(int n, int k, int64_t rows, const int32_t *desc, c
     row_ptr[rows] = at;
     return at;
 }
+
+/* ---- several input channels, one output (the "multi-channel context" the paper
+ * names as future work, Section 4.2) -----------------------------------------
+ * out = sum over channels ch of the padded, strided convolution of plane A_ch
+ * with kernel K_ch, i.e. [T_1 | ... | T_C] applied to the stacked vectors.
+ *   A   : C planes one after the other, each m*n*B floats, batch-minor.
+ *   K   : C kernels one after the other, each k*k floats, row-major.
+ * By definition: every plane is padded with zeros, then each output is the sum,
+ * over channels and over the window, of kernel number times padded value, carried
+ * in double and rounded once. */
+int oracle_conv_channels(int m, int n, int k, int s, int p, int B, int C,
+                         const float *A, const float *K, float *out, double *scale)
+{
+    int64_t mo, no;
+    if (B < 1 || C < 1 || oracle_out_shape(m, n, k, s, p, &mo, &no) != 0) return -1;
+    int64_t H = (int64_t)m + 2 * p, W = (int64_t)n + 2 * p;
+    float *Apad = (float *)calloc((size_t)(C * H * W * B), sizeof(float));
+    if (!Apad) return -2;
+    for (int64_t ch = 0; ch < C; ++ch)
+        for (int64_t i = 0; i < m; ++i)
+            memcpy(Apad + ((ch * H + i + p) * W + p) * B, A + (ch * m + i) * n * B, sizeof(float) * (size_t)n * B);
+
+#pragma omp parallel for schedule(static)
+    for (int64_t x = 0; x < mo; ++x) {
+        for (int64_t y = 0; y < no; ++y) {
+            for (int64_t c = 0; c < B; ++c) {
+                double acc = 0.0, mag = 0.0;
+                for (int64_t ch = 0; ch < C; ++ch)
+                    for (int64_t a = 0; a < k; ++a)
+                        for (int64_t b = 0; b < k; ++b) {
+                            double kv = (double)K[(ch * k + a) * k + b];
+                            double av = (double)Apad[(((ch * H) + s * x + a) * W + (s * y + b)) * B + c];
+                            acc += kv * av;
+                            mag += fabs(kv) * fabs(av);
+                        }
+                out[(x * no + y) * B + c] = (float)acc;
+                if (scale) scale[(x * no + y) * B + c] = mag;
+            }
+        }
+    }
+    free(Apad);
+    return 0;
+}
