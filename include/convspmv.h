@@ -74,6 +74,26 @@ int conv_csr_build(int m, int n, int k, int s, int p,
                    int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev,
                    void *stream, conv_plan **plan_out);
 
+/* Several input channels, one output (the multi-channel context the paper
+ * names as an outlook, Section 4.2): y = sum over ch of T_ch x_ch, i.e. the
+ * horizontally concatenated matrix [T_1 | ... | T_C] applied to the stacked
+ * input planes.  All T_ch have the same shape and therefore the same row_ptr
+ * and col_idx (Section 2: the positions depend on m, n, k, s, p only); they
+ * differ in their values.  Stored as one row_ptr, one col_idx and
+ *   vals_dev    : channels*nnz fp32, device, written: the values of T_ch at
+ *                 vals_dev + ch*nnz,
+ * from
+ *   kernels_dev : channels*k*k fp32, device: kernel ch at kernels_dev + ch*k*k.
+ * conv_spmv on the plan takes x_dev of channels*m*n*batch elements (plane ch,
+ * batch-minor, at x_dev + ch*m*n*batch) and writes y_dev of m_out*n_out*batch
+ * elements; conv_update_kernel takes channels*k*k numbers.  channels = 1 is
+ * conv_csr_build.  conv_multi_create does not accept a plan with more than one
+ * channel.  Everything else as for conv_csr_build. */
+int conv_csr_build_channels(int m, int n, int k, int s, int p, int channels,
+                            const float *kernels_dev,
+                            int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev,
+                            void *stream, conv_plan **plan_out);
+
 /* Build T column-compressed (CSC), the other storage the paper uses
  * (Sections 3 and 4.1).  The CSC arrays of T are the CSR arrays of T^T:
  *   col_ptr_dev : (m*n + 1) int32, device, written.
@@ -147,6 +167,7 @@ int conv_plan_shape(const conv_plan *plan, int *m, int *n, int *k, int *s, int *
                     int *m_out, int *n_out, int64_t *nnz);
 int conv_plan_is_transposed(const conv_plan *plan);
 int conv_plan_is_compact(const conv_plan *plan);
+int conv_plan_channels(const conv_plan *plan);      /* input channels (1 unless built by conv_csr_build_channels) */
 
 /* Name of the apply variant conv_spmv would launch for this batch with
  * 16-byte-aligned x and y (for reports), or NULL on bad arguments.  The text

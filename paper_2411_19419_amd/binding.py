@@ -23,6 +23,7 @@ EXPORTS = (
     "conv_multi_create", "conv_multi_apply", "conv_multi_destroy",
     "conv_csc_build", "conv_plan_is_transposed",
     "conv_compact_build", "conv_plan_is_compact",
+    "conv_csr_build_channels", "conv_plan_channels",
 )
 
 
@@ -63,6 +64,10 @@ def _load():
         lib.conv_compact_build.restype = i
         lib.conv_plan_is_compact.argtypes = [vp]
         lib.conv_plan_is_compact.restype = i
+        lib.conv_csr_build_channels.argtypes = [i, i, i, i, i, i, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]
+        lib.conv_csr_build_channels.restype = i
+        lib.conv_plan_channels.argtypes = [vp]
+        lib.conv_plan_channels.restype = i
         lib.conv_spmv.argtypes = [vp, vp, vp, i, vp]
         lib.conv_spmv.restype = i
         lib.conv_plan_shape.argtypes = [vp, pi, pi, pi, pi, pi, pi, pi, pi64]
@@ -138,6 +143,7 @@ class ConvPlan:
         self._kernel = kernel           # keep K alive until the build has run
         self.compact = False
         self.row_desc = self.ktab = None   # structure-aware storage (conv_compact_build)
+        self.channels = 1                  # input channels sharing the indices (conv_csr_build_channels)
 
     @property
     def rows(self):
@@ -145,7 +151,7 @@ class ConvPlan:
 
     @property
     def cols(self):
-        return self.m_out * self.n_out if self.transposed else self.m * self.n
+        return self.m_out * self.n_out if self.transposed else self.m * self.n * self.channels
 
     def variant(self, batch: int) -> str:
         v = _load().conv_spmv_variant(self._handle, int(batch))
@@ -156,7 +162,8 @@ class ConvPlan:
         x once, y once."""
         if self.compact:    # descriptors and the value table instead of the entries
             return self.rows * 8 + self.k * self.k * 4 + self.cols * batch * 4 + self.rows * batch * 4
-        return self.nnz * 8 + (self.rows + 1) * 4 + self.cols * batch * 4 + self.rows * batch * 4
+        return (self.nnz * 4 * (1 + self.channels) + (self.rows + 1) * 4 + self.cols * batch * 4
+                + self.rows * batch * 4)
 
     def close(self):
         if self._handle is not None:
@@ -203,6 +210,34 @@ def conv_csr_build(m, n, k, s, p, kernel, stream=None, _transposed=False) -> Con
     return ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, row_ptr, col_idx, vals, kernel, transposed=_transposed)
 
 
+def conv_csr_build_channels(m, n, k, s, p, kernels, channels, stream=None) -> ConvPlan:
+    """Build [T_1 | ... | T_C]: shared row_ptr / col_idx, plan.vals holds `channels` arrays of nnz
+    values one after the other.  `kernels`: channels*k*k float32 device tensor."""
+    import torch
+    lib = _load()
+    mo, no = conv_out_shape(m, n, k, s, p)
+    nnz = conv_nnz(m, n, k, s, p)
+    if not (kernels.is_cuda and kernels.dtype == torch.float32 and kernels.is_contiguous()
+            and channels >= 1 and kernels.numel() == channels * k * k):
+        raise ValueError("kernels must be a contiguous float32 device tensor with channels*k*k elements")
+    dev = kernels.device
+    if nnz >= 2 ** 31 or mo * no >= 2 ** 31 - 1 or m * n * channels >= 2 ** 31 - 1:
+        raise ConvError(-3, "conv_csr_build_channels%r" % ((m, n, k, s, p, channels),))
+    row_ptr = torch.empty(mo * no + 1, dtype=torch.int32, device=dev)
+    col_idx = torch.empty(max(nnz, 1), dtype=torch.int32, device=dev)[:nnz]
+    vals = torch.empty(max(nnz * channels, 1), dtype=torch.float32, device=dev)[:nnz * channels]
+    handle = ctypes.c_void_p()
+    with torch.cuda.device(dev):
+        sh, _ = _stream_handle(stream)
+        st = lib.conv_csr_build_channels(m, n, k, s, p, int(channels), kernels.data_ptr(), row_ptr.data_ptr(),
+                                         col_idx.data_ptr(), vals.data_ptr(), sh, ctypes.byref(handle))
+    if st != 0:
+        raise ConvError(st, "conv_csr_build_channels%r" % ((m, n, k, s, p, channels),))
+    plan = ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, row_ptr, col_idx, vals, kernels)
+    plan.channels = int(channels)
+    return plan
+
+
 def conv_compact_build(m, n, k, s, p, kernel, stream=None) -> ConvPlan:
     """Build T in the structure-aware storage: plan.row_desc is int32 (rows, 2) = per row the
     column of its first entry and the packed tap ranges, plan.ktab the k*k value table."""
@@ -237,8 +272,8 @@ def conv_update_kernel(plan: ConvPlan, kernel, stream=None) -> None:
     if plan._handle is None:
         raise ValueError("plan is closed")
     if not (kernel.is_cuda and kernel.dtype == torch.float32 and kernel.is_contiguous()
-            and kernel.numel() == plan.k * plan.k):
-        raise ValueError("kernel must be a contiguous float32 device tensor with k*k elements")
+            and kernel.numel() == plan.k * plan.k * plan.channels):
+        raise ValueError("kernel must be a contiguous float32 device tensor with channels*k*k elements")
     with torch.cuda.device(kernel.device):
         sh, _ = _stream_handle(stream)
         st = _load().conv_update_kernel(plan._handle, kernel.data_ptr(), sh)

@@ -22,10 +22,18 @@ namespace convspmv {
 // ---------------------------------------------------------------------------
 constexpr int kGatherThreads = 256;
 
+// Several input channels that share one index structure (the sum over channels of T_ch x_ch,
+// the multi-channel context of Section 4.2): channel ch has its values at vals + ch * vals
+// and its operand plane at x + ch * x, both in elements.  One channel: strides unused.
+struct ChannelStrides {
+    int channels;
+    long long vals, x;
+};
+
 template <int G>
 __global__ __launch_bounds__(kGatherThreads) void spmm_gather_scalar_kernel(
     const int *__restrict__ row_ptr, const int *__restrict__ col_idx, const float *__restrict__ vals,
-    const float *__restrict__ x, float *__restrict__ y, int rows, int batch) {
+    const float *__restrict__ x, float *__restrict__ y, int rows, int batch, ChannelStrides cs) {
     const long long row = ((long long)blockIdx.x * kGatherThreads + threadIdx.x) / G;
     const int lane = (int)threadIdx.x % G;
     int beg = 0, end = 0;
@@ -35,8 +43,11 @@ __global__ __launch_bounds__(kGatherThreads) void spmm_gather_scalar_kernel(
     }
     for (int c = blockIdx.y; c < batch; c += gridDim.y) {   // uniform over the block
         float acc = 0.0f;
-        for (int e = beg + lane; e < end; e += G)
-            acc = fmaf(vals[e], x[(long long)col_idx[e] * batch + c], acc);
+        for (int e = beg + lane; e < end; e += G) {
+            const long long at = (long long)col_idx[e] * batch + c;
+            for (int ch = 0; ch < cs.channels; ++ch)
+                acc = fmaf(vals[ch * cs.vals + e], x[ch * cs.x + at], acc);
+        }
         acc = group_sum<G>(acc);
         if (row < rows && lane == 0) y[row * batch + c] = acc;
     }
@@ -45,7 +56,7 @@ __global__ __launch_bounds__(kGatherThreads) void spmm_gather_scalar_kernel(
 template <int G, int NV>
 __global__ __launch_bounds__(kGatherThreads) void spmm_gather_vec_kernel(
     const int *__restrict__ row_ptr, const int *__restrict__ col_idx, const float *__restrict__ vals,
-    const float *__restrict__ x, float *__restrict__ y, int rows, int batch) {
+    const float *__restrict__ x, float *__restrict__ y, int rows, int batch, ChannelStrides cs) {
     const long long row = ((long long)blockIdx.x * kGatherThreads + threadIdx.x) / G;
     const int lane = (int)threadIdx.x % G;
     int beg = 0, end = 0;
@@ -58,15 +69,18 @@ __global__ __launch_bounds__(kGatherThreads) void spmm_gather_vec_kernel(
 #pragma unroll
         for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int e = beg + lane; e < end; e += G) {
-            const float w = vals[e];
-            const float4 *xr = reinterpret_cast<const float4 *>(x + (long long)col_idx[e] * batch + c0);
+            const long long at = (long long)col_idx[e] * batch + c0;
+            for (int ch = 0; ch < cs.channels; ++ch) {
+                const float w = vals[ch * cs.vals + e];
+                const float4 *xr = reinterpret_cast<const float4 *>(x + ch * cs.x + at);
 #pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                const float4 xv = xr[v];
-                acc[v].x = fmaf(w, xv.x, acc[v].x);
-                acc[v].y = fmaf(w, xv.y, acc[v].y);
-                acc[v].z = fmaf(w, xv.z, acc[v].z);
-                acc[v].w = fmaf(w, xv.w, acc[v].w);
+                for (int v = 0; v < NV; ++v) {
+                    const float4 xv = xr[v];
+                    acc[v].x = fmaf(w, xv.x, acc[v].x);
+                    acc[v].y = fmaf(w, xv.y, acc[v].y);
+                    acc[v].z = fmaf(w, xv.z, acc[v].z);
+                    acc[v].w = fmaf(w, xv.w, acc[v].w);
+                }
             }
         }
 #pragma unroll

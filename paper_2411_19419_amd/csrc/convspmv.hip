@@ -65,6 +65,7 @@ struct conv_plan {
     int *axis_tab;            // owned, device: the two per-axis prefix tables of the build
     int device;
     bool transposed;          // the arrays hold T^T (CSC of T): rows = m*n, cols = m_out*n_out
+    int channels;             // input channels sharing row_ptr / col_idx; vals holds `channels` arrays of nnz
     bool compact;             // structure-aware storage: desc and ktab instead of the CSR arrays
     const int2 *desc;         // borrowed, device: one descriptor per row
     float *ktab;              // borrowed, device: k*k values (rewritten by conv_update_kernel)
@@ -99,17 +100,19 @@ int64_t conv_nnz(int m, int n, int k, int s, int p) {
 namespace {
 
 template <bool TR>
-int build_impl(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *ptr_dev, int32_t *idx_dev,
-               float *vals_dev, void *stream, conv_plan **plan_out) {
+int build_impl(int m, int n, int k, int s, int p, int channels, const float *kernel_dev, int32_t *ptr_dev,
+               int32_t *idx_dev, float *vals_dev, void *stream, conv_plan **plan_out) {
     if (!plan_out) return CONV_ENULL;
     *plan_out = nullptr;
     int64_t mo, no;
     int st = check_shape(m, n, k, s, p, &mo, &no);
     if (st != CONV_OK) return st;
+    if (channels < 1) return CONV_EINVAL;
     const int64_t nnz = conv_nnz(m, n, k, s, p);
     if (nnz < 0) return (int)nnz;
     const int64_t out_pixels = mo * no, in_pixels = (int64_t)m * n;
-    const int64_t rows = TR ? in_pixels : out_pixels, cols = TR ? out_pixels : in_pixels;
+    const int64_t rows = TR ? in_pixels : out_pixels, cols = (TR ? out_pixels : in_pixels) * channels;
+    if (cols >= kInt32Limit) return CONV_EOVERFLOW;
     const int64_t l1 = TR ? m : mo, l2 = TR ? n : no;        // lines of the matrix, rows per line
     // 32-bit indices: entries, columns, rows (+1 for the pointer array), the per-axis
     // prefix sums, and the grids of the build kernels.
@@ -136,6 +139,7 @@ int build_impl(int m, int n, int k, int s, int p, const float *kernel_dev, int32
     plan->axis_tab = nullptr;
     plan->device = 0;
     plan->transposed = TR;
+    plan->channels = channels;
     plan->compact = false;
     plan->desc = nullptr;
     plan->ktab = nullptr;
@@ -150,9 +154,13 @@ int build_impl(int m, int n, int k, int s, int p, const float *kernel_dev, int32
     hipStream_t q = (hipStream_t)stream;
     axis_prefix_kernel<TR><<<2, kAxisThreads, 0, q>>>(plan->shape, plan->axis_tab);
     row_ptr_kernel<TR><<<(unsigned)rp_blocks, kRowPtrThreads, 0, q>>>(plan->shape, plan->axis_tab, ptr_dev);
-    if (nnz > 0)
+    if (nnz > 0) {
         csr_fill_kernel<true, TR><<<(unsigned)fill_blocks, kFillThreads, 0, q>>>(plan->shape, plan->axis_tab,
                                                                                kernel_dev, idx_dev, vals_dev);
+        for (int ch = 1; ch < channels; ++ch)      // the other channels share the indices: values only
+            csr_fill_kernel<false, TR><<<(unsigned)fill_blocks, kFillThreads, 0, q>>>(
+                plan->shape, plan->axis_tab, kernel_dev + (size_t)ch * k * k, nullptr, vals_dev + (size_t)ch * nnz);
+    }
     if (!hip_ok(hipGetLastError())) {
         (void)hipFree(plan->axis_tab);
         delete plan;
@@ -168,12 +176,19 @@ extern "C" {
 
 int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *row_ptr_dev,
                    int32_t *col_idx_dev, float *vals_dev, void *stream, conv_plan **plan_out) {
-    return build_impl<false>(m, n, k, s, p, kernel_dev, row_ptr_dev, col_idx_dev, vals_dev, stream, plan_out);
+    return build_impl<false>(m, n, k, s, p, 1, kernel_dev, row_ptr_dev, col_idx_dev, vals_dev, stream, plan_out);
+}
+
+int conv_csr_build_channels(int m, int n, int k, int s, int p, int channels, const float *kernels_dev,
+                            int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev, void *stream,
+                            conv_plan **plan_out) {
+    return build_impl<false>(m, n, k, s, p, channels, kernels_dev, row_ptr_dev, col_idx_dev, vals_dev, stream,
+                             plan_out);
 }
 
 int conv_csc_build(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *col_ptr_dev,
                    int32_t *row_idx_dev, float *vals_dev, void *stream, conv_plan **plan_out) {
-    return build_impl<true>(m, n, k, s, p, kernel_dev, col_ptr_dev, row_idx_dev, vals_dev, stream, plan_out);
+    return build_impl<true>(m, n, k, s, p, 1, kernel_dev, col_ptr_dev, row_idx_dev, vals_dev, stream, plan_out);
 }
 
 int conv_compact_build(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *row_desc_dev,
@@ -207,6 +222,7 @@ int conv_compact_build(int m, int n, int k, int s, int p, const float *kernel_de
     plan->axis_tab = nullptr;
     plan->device = 0;
     plan->transposed = false;
+    plan->channels = 1;
     plan->compact = true;
     plan->desc = reinterpret_cast<const int2 *>(row_desc_dev);
     plan->ktab = ktab_dev;
@@ -236,12 +252,15 @@ int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream) {
     const int64_t l1 = plan->transposed ? plan->shape.m : plan->shape.m_out;
     const int64_t l2 = plan->transposed ? plan->shape.n : plan->shape.n_out;
     const unsigned fill_blocks = (unsigned)(l1 * ((l2 + kFillRows - 1) / kFillRows));
-    if (plan->transposed)
-        csr_fill_kernel<false, true><<<fill_blocks, kFillThreads, 0, (hipStream_t)stream>>>(
-            plan->shape, plan->axis_tab, kernel_dev, nullptr, plan->vals);
-    else
-        csr_fill_kernel<false, false><<<fill_blocks, kFillThreads, 0, (hipStream_t)stream>>>(
-            plan->shape, plan->axis_tab, kernel_dev, nullptr, plan->vals);
+    const size_t kk = (size_t)plan->shape.k * plan->shape.k;
+    for (int ch = 0; ch < plan->channels; ++ch) {
+        if (plan->transposed)
+            csr_fill_kernel<false, true><<<fill_blocks, kFillThreads, 0, (hipStream_t)stream>>>(
+                plan->shape, plan->axis_tab, kernel_dev + ch * kk, nullptr, plan->vals + (size_t)ch * plan->nnz);
+        else
+            csr_fill_kernel<false, false><<<fill_blocks, kFillThreads, 0, (hipStream_t)stream>>>(
+                plan->shape, plan->axis_tab, kernel_dev + ch * kk, nullptr, plan->vals + (size_t)ch * plan->nnz);
+    }
     if (!hip_ok(hipGetLastError())) return CONV_EHIP;
     return CONV_OK;
 }
@@ -419,6 +438,7 @@ ApplyChoice choose_apply(const conv_plan *plan, const float *x, const float *y, 
     c.nv = !vec ? 0 : (batch % 16 == 0 ? 4 : (batch % 8 == 0 ? 2 : 1));
     c.kind = vec ? Kind::GatherVec : Kind::GatherScalar;
     if (plan->nnz == 0 || (!vec && batch != 1) || (vec && batch / (4 * c.nv) > 65535)) return c;
+    if (plan->channels > 1) return c;           // the LDS kernels stage one operand plane
 
     // marching kernel: float4 column chunks, or one scalar column for a single vector (SpMV)
     MarchShape ms;
@@ -467,22 +487,23 @@ void launch_gather(const ApplyChoice &c, const conv_plan *plan, const float *x, 
     const int rows = (int)plan->rows;
     const unsigned bx = (unsigned)(((int64_t)rows * G + kGatherThreads - 1) / kGatherThreads);
     auto by = [&](int per) { int b = batch / per; return (unsigned)(b > 65535 ? 65535 : b); };
+    const ChannelStrides cs{plan->channels, (long long)plan->nnz, (long long)(plan->cols / plan->channels) * batch};
     switch (c.nv) {
         case 0:
             spmm_gather_scalar_kernel<G><<<dim3(bx, by(1)), kGatherThreads, 0, q>>>(
-                plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch);
+                plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch, cs);
             break;
         case 1:
             spmm_gather_vec_kernel<G, 1><<<dim3(bx, by(4)), kGatherThreads, 0, q>>>(
-                plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch);
+                plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch, cs);
             break;
         case 2:
             spmm_gather_vec_kernel<G, 2><<<dim3(bx, by(8)), kGatherThreads, 0, q>>>(
-                plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch);
+                plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch, cs);
             break;
         default:
             spmm_gather_vec_kernel<G, 4><<<dim3(bx, by(16)), kGatherThreads, 0, q>>>(
-                plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch);
+                plan->row_ptr, plan->col_idx, plan->vals, x, y, rows, batch, cs);
             break;
     }
 }
@@ -756,7 +777,7 @@ int conv_multi_create(int n, const conv_plan *const *plans, const float *const *
     for (int i = 0; i < n && status == CONV_OK; ++i) {
         const conv_plan *p = plans[i];
         if (!p || !x_dev[i] || !y_dev[i]) { status = CONV_ENULL; break; }
-        if (p->device != plans[0]->device || p->compact) { status = CONV_EINVAL; break; }
+        if (p->device != plans[0]->device || p->compact || p->channels != 1) { status = CONV_EINVAL; break; }
         const char *xb = (const char *)x_dev[i], *xe = xb + sizeof(float) * (size_t)p->cols * batch;
         const char *yb = (const char *)y_dev[i], *ye = yb + sizeof(float) * (size_t)p->rows * batch;
         if (xb < ye && yb < xe) { status = CONV_EALIAS; break; }
@@ -834,6 +855,7 @@ int conv_plan_shape(const conv_plan *plan, int *m, int *n, int *k, int *s, int *
 
 int conv_plan_is_transposed(const conv_plan *plan) { return plan ? (plan->transposed ? 1 : 0) : CONV_ENULL; }
 int conv_plan_is_compact(const conv_plan *plan) { return plan ? (plan->compact ? 1 : 0) : CONV_ENULL; }
+int conv_plan_channels(const conv_plan *plan) { return plan ? plan->channels : CONV_ENULL; }
 
 const char *conv_spmv_variant(const conv_plan *plan, int batch) {
     if (!plan || batch < 1) return nullptr;

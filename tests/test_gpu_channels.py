@@ -1,0 +1,111 @@
+"""GPU parity for the multi-channel sum (conv_csr_build_channels): shared indices and the
+per-channel values bit-exact against the CSR oracle, y = sum_ch T_ch x_ch against the
+oracle's sum of padded convolutions."""
+import ctypes
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2411_19419_amd as cs
+from paper_2411_19419_amd import binding
+
+from gpu_util import REL_TOL, build_plan, device
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(shape, channels, batch, seed):
+    m, n, k, s, p = shape
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal(channels * m * n * batch).astype(np.float32),
+            rng.standard_normal(channels * k * k).astype(np.float32))
+
+
+def _check(shape, channels, batch, seed=1, x_off=0):
+    m, n, k, s, p = shape
+    x, K = _case(shape, channels, batch, seed)
+    plan = cs.conv_csr_build_channels(m, n, k, s, p, torch.from_numpy(K).to(device()), channels)
+    assert binding._load().conv_plan_channels(plan._handle) == channels
+    rp, ci, _ = oracle.csr(m, n, k, s, p, K[:k * k])
+    assert np.array_equal(plan.row_ptr.cpu().numpy().astype(np.int64), rp)
+    assert np.array_equal(plan.col_idx.cpu().numpy().astype(np.int64), ci)
+    vals = plan.vals.cpu().numpy().reshape(channels, -1)
+    for ch in range(channels):
+        want = oracle.csr(m, n, k, s, p, K[ch * k * k:(ch + 1) * k * k])[2]
+        assert np.array_equal(vals[ch].view(np.uint32), want.view(np.uint32)), "vals of channel %d differ" % ch
+    buf = torch.zeros(x.size + x_off, dtype=torch.float32, device=device())
+    buf[x_off:] = torch.from_numpy(x).to(device())
+    y = torch.full((plan.rows * batch,), float("nan"), dtype=torch.float32, device=device())
+    cs.conv_spmv(plan, buf[x_off:], y, batch=batch)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    ref, scale = oracle.conv_channels(m, n, k, s, p, x, K, channels, batch=batch, want_scale=True)
+    assert not np.any(np.isnan(got))
+    live = scale > 0
+    assert np.all(got[~live] == 0.0)
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    assert (np.max(err[live] / scale[live]) if np.any(live) else 0.0) <= REL_TOL
+    return plan, x, K
+
+
+@pytest.mark.parametrize("shape,channels,batch", [
+    ((37, 53, 7, 1, 3), 3, 16), ((130, 67, 7, 1, 3), 2, 4), ((100, 90, 5, 2, 2), 4, 8), ((33, 200, 3, 1, 1), 8, 1),
+    ((75, 75, 9, 3, 8), 2, 3), ((40, 40, 13, 1, 6), 3, 5), ((6, 6, 2, 1, 5), 5, 7), ((1, 1, 1, 5, 2), 4, 3),
+    ((224, 224, 7, 2, 3), 3, 16), ((56, 56, 3, 1, 1), 64, 4), ((300, 301, 2, 2, 0), 2, 12), ((64, 64, 3, 1, 1), 1, 16),
+])
+def test_channel_sum_matches_oracle(shape, channels, batch):
+    plan, _, _ = _check(shape, channels, batch)
+    plan.close()
+
+
+def test_channel_sum_unaligned_operand():
+    plan, _, _ = _check((50, 70, 5, 1, 2), 3, 4, seed=2, x_off=1)
+    plan.close()
+
+
+def test_one_channel_is_the_plain_build():
+    shape, batch = (90, 120, 7, 1, 3), 16
+    m, n, k, s, p = shape
+    x, K = _case(shape, 1, batch, 3)
+    a = cs.conv_csr_build_channels(m, n, k, s, p, torch.from_numpy(K).to(device()), 1)
+    b = build_plan(shape, K)
+    assert torch.equal(a.row_ptr, b.row_ptr) and torch.equal(a.col_idx, b.col_idx) and torch.equal(a.vals, b.vals)
+    xd = torch.from_numpy(x).to(device())
+    assert a.variant(batch) == b.variant(batch)
+    assert torch.equal(cs.conv_spmv(a, xd, batch=batch), cs.conv_spmv(b, xd, batch=batch))
+    a.close()
+    b.close()
+
+
+def test_update_kernel_rewrites_every_channel():
+    shape, channels, batch = (60, 80, 5, 1, 2), 3, 8
+    m, n, k, s, p = shape
+    plan, x, _ = _check(shape, channels, batch, seed=4)
+    K2 = np.random.default_rng(5).standard_normal(channels * k * k).astype(np.float32)
+    cols_before = plan.col_idx.clone()
+    cs.conv_update_kernel(plan, torch.from_numpy(K2).to(device()))
+    y = cs.conv_spmv(plan, torch.from_numpy(x).to(device()), batch=batch)
+    torch.cuda.synchronize()
+    assert torch.equal(cols_before, plan.col_idx)
+    ref, scale = oracle.conv_channels(m, n, k, s, p, x, K2, channels, batch=batch, want_scale=True)
+    err = np.abs(y.cpu().numpy().astype(np.float64) - ref)
+    assert np.max(err / np.maximum(scale, 1e-30)) <= REL_TOL
+    plan.close()
+
+
+def test_channel_errors():
+    lib = binding._load()
+    dev = device()
+    K = torch.ones(18, device=dev)
+    h = ctypes.c_void_p()
+    assert lib.conv_csr_build_channels(4, 4, 3, 1, 1, 0, K.data_ptr(), 16, 16, 16, None, ctypes.byref(h)) == -1
+    plan = cs.conv_csr_build_channels(8, 8, 3, 1, 1, K, 2)
+    x = torch.zeros(128, device=dev)
+    y = torch.zeros(64, device=dev)
+    with pytest.raises(cs.ConvError):               # the fused multi-product launch takes one-channel plans
+        cs.ConvMulti([plan], [x], [y], batch=1)
+    with pytest.raises(ValueError):                 # x must hold both planes
+        cs.conv_spmv(plan, torch.zeros(64, device=dev), y, batch=1)
+    plan.close()
