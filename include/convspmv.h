@@ -156,8 +156,11 @@ int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream);
  * The kernels read row_ptr, col_idx and vals as stored: the result is the
  * product with whatever the three arrays hold, provided row_ptr is still
  * non-decreasing with row lengths <= k*k and every col_idx is in [0, m*n).
- * fp32 multiply-add, summation order unspecified but fixed (no atomics):
- * repeated calls give bit-identical results.  x and y must not overlap. */
+ * fp32 multiply-add, summation order unspecified but fixed: repeated calls
+ * give bit-identical results.  (A plan with several channels may run one
+ * kernel per channel on `stream`, the later ones adding to y with one
+ * hardware float add per element; the order of those adds is the launch
+ * order.)  x and y must not overlap. */
 int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch, void *stream);
 
 /* Shape and size queries on a plan (host only).  conv_plan_is_transposed

@@ -43,10 +43,20 @@ __global__ __launch_bounds__(kGatherThreads) void spmm_gather_scalar_kernel(
     }
     for (int c = blockIdx.y; c < batch; c += gridDim.y) {   // uniform over the block
         float acc = 0.0f;
-        for (int e = beg + lane; e < end; e += G) {
-            const long long at = (long long)col_idx[e] * batch + c;
-            for (int ch = 0; ch < cs.channels; ++ch)
-                acc = fmaf(vals[ch * cs.vals + e], x[ch * cs.x + at], acc);
+        if (cs.channels == 1) {
+            for (int e = beg + lane; e < end; e += G)
+                acc = fmaf(vals[e], x[(long long)col_idx[e] * batch + c], acc);
+        } else if (end > beg) {
+            // the group walks the row's entries of all channels as one list: position t is
+            // entry t % len of channel t / len
+            const int len = end - beg;
+            int ch = lane / len, eo = lane - ch * len;
+            while (ch < cs.channels) {
+                const int e = beg + eo;
+                acc = fmaf(vals[ch * cs.vals + e], x[ch * cs.x + (long long)col_idx[e] * batch + c], acc);
+                eo += G;
+                while (eo >= len) { eo -= len; ++ch; }
+            }
         }
         acc = group_sum<G>(acc);
         if (row < rows && lane == 0) y[row * batch + c] = acc;
@@ -68,19 +78,29 @@ __global__ __launch_bounds__(kGatherThreads) void spmm_gather_vec_kernel(
         float4 acc[NV];
 #pragma unroll
         for (int v = 0; v < NV; ++v) acc[v] = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int e = beg + lane; e < end; e += G) {
-            const long long at = (long long)col_idx[e] * batch + c0;
-            for (int ch = 0; ch < cs.channels; ++ch) {
-                const float w = vals[ch * cs.vals + e];
-                const float4 *xr = reinterpret_cast<const float4 *>(x + ch * cs.x + at);
+        auto add = [&](float w, const float4 *xr) {
 #pragma unroll
-                for (int v = 0; v < NV; ++v) {
-                    const float4 xv = xr[v];
-                    acc[v].x = fmaf(w, xv.x, acc[v].x);
-                    acc[v].y = fmaf(w, xv.y, acc[v].y);
-                    acc[v].z = fmaf(w, xv.z, acc[v].z);
-                    acc[v].w = fmaf(w, xv.w, acc[v].w);
-                }
+            for (int v = 0; v < NV; ++v) {
+                const float4 xv = xr[v];
+                acc[v].x = fmaf(w, xv.x, acc[v].x);
+                acc[v].y = fmaf(w, xv.y, acc[v].y);
+                acc[v].z = fmaf(w, xv.z, acc[v].z);
+                acc[v].w = fmaf(w, xv.w, acc[v].w);
+            }
+        };
+        if (cs.channels == 1) {
+            for (int e = beg + lane; e < end; e += G)
+                add(vals[e], reinterpret_cast<const float4 *>(x + (long long)col_idx[e] * batch + c0));
+        } else if (end > beg) {
+            // the group walks the row's entries of all channels as one list (see the scalar kernel)
+            const int len = end - beg;
+            int ch = lane / len, eo = lane - ch * len;
+            while (ch < cs.channels) {
+                const int e = beg + eo;
+                add(vals[ch * cs.vals + e],
+                    reinterpret_cast<const float4 *>(x + ch * cs.x + (long long)col_idx[e] * batch + c0));
+                eo += G;
+                while (eo >= len) { eo -= len; ++ch; }
             }
         }
 #pragma unroll

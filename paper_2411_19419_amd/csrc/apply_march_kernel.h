@@ -50,6 +50,7 @@ struct MarchGeom {
     int iw;               // operand columns a strip can touch (upper bound): (TW-1)*s + k, or (TW-2+k)/s + 2 for T^T
     int iw_pitch;         // LDS pixels per ring line (>= iw)
     float inv_n;          // 1.0f / n
+    int accum;            // 1: add to y instead of storing (later channels of a multi-channel sum)
 };
 
 // NV: float4 column chunks per lane (NV planes in LDS, 4*NV batch columns per
@@ -265,7 +266,7 @@ __global__ __launch_bounds__(512, 4) void spmm_march_kernel(const int *__restric
         const int yy = wave * RW + gr;
         if (xo < xb && yy < twc && (gl & ((1 << DUP) - 1)) == 0) {
             float *dst = y + ((long long)xo * g.n_out + (y0 + yy)) * g.batch + c0 + (gl >> DUP) * CNT;
-            store_row<CNT>(dst, acc);
+            store_row<CNT>(dst, acc, g.accum != 0);
         }
     };
 

@@ -37,6 +37,7 @@ struct TileGeom {
     int ih, iw;           // input extent a full tile can touch: (th-1)*s+k, (TW-1)*s+k
     int iw_pitch;         // LDS pixels per input line (>= iw); ih*iw_pitch < CS (template)
     float inv_n;          // 1.0f / n
+    int accum;            // 1: add to y instead of storing
 };
 
 constexpr int kXcds = 8;  // MI355X: workgroups are dealt round-robin to 8 XCDs, each with its own L2
@@ -81,10 +82,20 @@ __device__ __forceinline__ float stream_load_f(const float *base, unsigned off) 
 // on this part cost about a quarter less time than plain ones next to the
 // entry stream (measured with a traffic-only probe: 67 MB of y add 22 us
 // instead of 30 us to a 66 us read stream).
+//
+// accum: add to y instead (one hardware float add per element, no return value, so the wave
+// does not wait for it).  Used for the second and later channels of a multi-channel sum, one
+// launch per channel on one stream: every element of y then receives exactly one add per
+// launch, in launch order, and the result does not depend on timing.
 template <int CNT, int LEN>
-__device__ __forceinline__ void store_row(float *dst, const float (&a)[LEN]) {
+__device__ __forceinline__ void store_row(float *dst, const float (&a)[LEN], bool accum = false) {
     typedef float vec2 __attribute__((ext_vector_type(2)));
     typedef float vec4 __attribute__((ext_vector_type(4)));
+    if (accum) {
+#pragma unroll
+        for (int i = 0; i < CNT; ++i) unsafeAtomicAdd(dst + i, a[i]);
+        return;
+    }
     if constexpr (CNT == 1) {
         __builtin_nontemporal_store(a[0], dst);
     } else if constexpr (CNT == 2) {
@@ -296,7 +307,7 @@ __global__ __launch_bounds__(TW * 8) void spmm_tile_kernel(const int *__restrict
         const int line = pid / GPL, yy = (pid % GPL) * RW + gr;
         if (line < thc && yy < twc && (gl & ((1 << DUP) - 1)) == 0) {
             float *dst = y + ((long long)(x0 + line) * g.n_out + (y0 + yy)) * g.batch + c0 + (gl >> DUP) * CNT;
-            store_row<CNT>(dst, acc);
+            store_row<CNT>(dst, acc, g.accum != 0);
         }
     };
 

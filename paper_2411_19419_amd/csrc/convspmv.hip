@@ -4,8 +4,10 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cstdio>
+#include <cstring>
 #include <new>
 
 #include "apply_kernels.h"
@@ -429,16 +431,22 @@ bool march_geometry(const conv_plan *plan, int batch, int nv, int tw, MarchGeom 
     return true;
 }
 
-ApplyChoice choose_apply(const conv_plan *plan, const float *x, const float *y, int batch) {
+ApplyChoice choose_apply(const conv_plan *full, const float *x, const float *y, int batch) {
+    // geometry of one channel; a multi-channel plan applies it once per channel (LDS kernels)
+    // or walks the channels inside the row-group kernels
+    conv_plan one = *full;
+    one.cols = full->cols / full->channels;
+    one.channels = 1;
+    const conv_plan *plan = &one;
     ApplyChoice c{};
     const bool aligned = ((((uintptr_t)x) | ((uintptr_t)y)) & 15u) == 0;
-    c.g = group_width(plan->max_row_nnz);
+    // (a multi-channel row is walked as one list of channels * entries by the row-group kernels)
+    c.g = group_width((int)std::min<int64_t>((int64_t)plan->max_row_nnz * full->channels, 1 << 20));
     c.threads = kGatherThreads;
     const bool vec = aligned && batch % 4 == 0;
     c.nv = !vec ? 0 : (batch % 16 == 0 ? 4 : (batch % 8 == 0 ? 2 : 1));
     c.kind = vec ? Kind::GatherVec : Kind::GatherScalar;
     if (plan->nnz == 0 || (!vec && batch != 1) || (vec && batch / (4 * c.nv) > 65535)) return c;
-    if (plan->channels > 1) return c;           // the LDS kernels stage one operand plane
 
     // marching kernel: float4 column chunks, or one scalar column for a single vector (SpMV)
     MarchShape ms;
@@ -457,6 +465,10 @@ ApplyChoice choose_apply(const conv_plan *plan, const float *x, const float *y, 
         return c;
     }
     if (!vec || plan->transposed) return c;     // the tile kernel is laid out for T only
+    // A multi-channel sum through the LDS kernels is one launch per channel.  That pays for the
+    // marching kernel (large problems); the problems the tile kernel takes are small, and the
+    // row-group kernels, which walk the channels inside one launch, measured 3x faster there.
+    if (full->channels > 1) return c;
 
     // one LDS tile per workgroup when the rows fit its unrolled trip count and the
     // input window of at least one output line fits the LDS planes
@@ -734,10 +746,20 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
         return hip_ok(hipGetLastError()) ? CONV_OK : CONV_EHIP;
     }
     const ApplyChoice c = choose_apply(plan, x_dev, y_dev, batch);
-    if (c.kind == Kind::March) {
-        if (!launch_march(c, plan, x_dev, y_dev, q)) return CONV_EHIP;
-    } else if (c.kind == Kind::Tile) {
-        if (!launch_tile(c, plan, x_dev, y_dev, q)) return CONV_EHIP;
+    if (c.kind == Kind::March || c.kind == Kind::Tile) {
+        // one launch per channel: the first stores y, the others add to it
+        conv_plan one = *plan;
+        one.cols = plan->cols / plan->channels;
+        one.channels = 1;
+        ApplyChoice cc = c;
+        for (int ch = 0; ch < plan->channels; ++ch) {
+            one.vals = plan->vals + (size_t)ch * plan->nnz;
+            const float *x_ch = x_dev + (size_t)ch * one.cols * batch;
+            cc.march.accum = cc.geom.accum = ch > 0;
+            const bool ok = c.kind == Kind::March ? launch_march(cc, &one, x_ch, y_dev, q)
+                                                  : launch_tile(cc, &one, x_ch, y_dev, q);
+            if (!ok) return CONV_EHIP;
+        }
     } else {
         switch (c.g) {
             case 1: launch_gather<1>(c, plan, x_dev, y_dev, batch, q); break;
@@ -887,6 +909,11 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch) {
         case Kind::Tile:
             snprintf(name, sizeof name, "lds_tile_%dx%d_g%d_nit%d_float4x%d", c.geom.th, c.tw, c.g, c.nit, c.nv);
             break;
+    }
+    if (plan->channels > 1) {
+        const size_t len = strlen(name);
+        const bool per_channel = c.kind == Kind::March || c.kind == Kind::Tile;
+        snprintf(name + len, sizeof name - len, per_channel ? "_x%d_launches" : "_%d_channels", plan->channels);
     }
     return name;
 }
