@@ -11,7 +11,7 @@ import oracle
 import paper_2411_19419_amd as cs
 from paper_2411_19419_amd import workloads
 
-from gpu_util import build_plan, check_apply, check_csr, device
+from gpu_util import REL_TOL, build_plan, check_apply, check_csr, device
 
 pytestmark = pytest.mark.gpu
 
@@ -402,3 +402,57 @@ def test_fused_apply_mixed_shapes_and_errors():
     assert ei.value.status == -6
     for pl in plans:
         pl.close()
+
+
+def test_largest_index_range():
+    """nnz just below 2^31 (the limit of the int32 indices): 6600 x 6600, k = 7, 'same' padding
+    gives 2 133 331 344 entries.  row_ptr is compared in full with the prefix sums of Theorem
+    2.1's row lengths, col_idx / vals on the first, last and 3000 random rows with the oracle's
+    tap enumeration, y in full with the sliding-window oracle; the structure-aware storage of
+    the same T likewise (descriptors in full)."""
+    shape, batch = (6600, 6600, 7, 1, 3), 1
+    m, n, k, s, p = shape
+    mo, no = oracle.out_shape(*shape)
+    nnz = oracle.nnz_closed(*shape)
+    assert 2 ** 31 - 2 ** 24 < nnz < 2 ** 31
+    rng = np.random.default_rng(31)
+    x = rng.standard_normal(m * n * batch).astype(np.float32)
+    K = rng.standard_normal(k * k).astype(np.float32)
+    plan = build_plan(shape, K)
+    assert plan.nnz == nnz
+    # row_ptr: exclusive prefix sums of r1(x) r2(y) (Theorem 2.1), in int64 on the host
+    t1, t2 = np.arange(mo, dtype=np.int64), np.arange(no, dtype=np.int64)
+    r1 = np.maximum(0, k - np.maximum(0, p - s * t1) - np.maximum(0, s * t1 + k - m - p))
+    r2 = np.maximum(0, k - np.maximum(0, p - s * t2) - np.maximum(0, s * t2 + k - n - p))
+    want = np.concatenate([[0], np.cumsum(np.outer(r1, r2).reshape(-1))])
+    assert want[-1] == nnz
+    got_rp = plan.row_ptr.cpu().numpy()
+    assert np.array_equal(got_rp.astype(np.int64), want)
+    del want
+    rows = np.unique(np.concatenate([np.arange(200), np.arange(mo * no - 200, mo * no),
+                                     rng.integers(0, mo * no, size=3000)]))
+    for r in rows:
+        cols, vals = oracle.csr_row(m, n, k, s, p, K, int(r))
+        lo, hi = int(got_rp[r]), int(got_rp[r + 1])
+        assert np.array_equal(plan.col_idx[lo:hi].cpu().numpy().astype(np.int64), cols), r
+        assert np.array_equal(plan.vals[lo:hi].cpu().numpy().view(np.uint32), vals.view(np.uint32)), r
+    xd = torch.from_numpy(x).to(device())
+    ref, scale = oracle.conv(m, n, k, s, p, x, K, batch=batch, want_scale=True)
+
+    def compare(pl):
+        y = torch.full((mo * no * batch,), float("nan"), dtype=torch.float32, device=device())
+        cs.conv_spmv(pl, xd, y, batch=batch)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        assert not np.any(np.isnan(got))
+        assert np.max(np.abs(got.astype(np.float64) - ref) / scale) <= REL_TOL
+
+    compare(plan)
+    print("largest: variant %s" % plan.variant(batch))
+    plan.close()
+    del plan
+    torch.cuda.empty_cache()
+    pc = cs.conv_compact_build(m, n, k, s, p, torch.from_numpy(K).to(device()))
+    assert np.array_equal(pc.row_desc.cpu().numpy(), oracle.compact_rows(*shape))
+    compare(pc)
+    pc.close()
