@@ -76,6 +76,7 @@ struct CompactGeom {
     int rv;               // output lines per step
     int nl;               // ring lines (power of two); 0: no ring, every tap is read from global memory
     int ktab_lds;         // 1: the table is copied to LDS behind the ring
+    int c_base;           // first batch column of this launch (wide batches take several launches)
 };
 
 constexpr int kCompactThreads = 256;
@@ -116,7 +117,7 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
     const int sg = job / g.strips, tx = job - sg * g.strips;
     const int y0 = tx * TW, xa = sg * g.seg, xb = min(xa + g.seg, g.m_out);
     const int twc = min(TW, g.n_out - y0);
-    const int c0 = blockIdx.y * NCOL;
+    const int c0 = g.c_base + blockIdx.y * NCOL;
     const int tid = threadIdx.x, yy = tid / LPR, v = tid % LPR;
 
     // ---- the ring holds the zero-padded plane: line i (any sign) in slot i mod NL, pixels

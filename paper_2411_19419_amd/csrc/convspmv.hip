@@ -636,7 +636,6 @@ CompactChoice choose_compact(const conv_plan *plan, const float *x, const float 
     c.scalar = !(aligned && batch % 4 == 0);
     c.lpr = c.scalar ? 1 : (batch % 16 == 0 ? 4 : (batch % 8 == 0 ? 2 : 1));
     const int ncol = c.scalar ? 1 : 4 * c.lpr, eb = c.scalar ? 4 : 16;
-    if (batch / ncol > 65535) return c;
     c.col_blocks = (unsigned)(batch / ncol);
     const int tw = kCompactThreads / c.lpr;
     CompactGeom g{};
@@ -702,8 +701,13 @@ bool launch_compact_inst(const CompactChoice &c, const conv_plan *plan, const fl
     auto kern = spmm_compact_kernel<KK, SS, LPR, SCALAR, FAST ? kRectRv : 0, FAST ? kRectNl : 0, FAST ? kRectXld : 0>;
     static thread_local bool allowed[64];
     if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
-    const dim3 grid((unsigned)(c.geom.blocks_per_xcd * kXcds), c.col_blocks);
-    kern<<<grid, kCompactThreads, c.lds, q>>>(plan->desc, plan->ktab, x, y, c.geom);
+    constexpr unsigned kMaxGridY = 65535;
+    CompactGeom g = c.geom;
+    for (unsigned cb = 0; cb < c.col_blocks; cb += kMaxGridY) {      // column blocks beyond the grid limit: more launches
+        g.c_base = (int)(cb * (SCALAR ? 1u : 4u * LPR));
+        const dim3 grid((unsigned)(c.geom.blocks_per_xcd * kXcds), std::min(kMaxGridY, c.col_blocks - cb));
+        kern<<<grid, kCompactThreads, c.lds, q>>>(plan->desc, plan->ktab, x, y, g);
+    }
     return true;
 }
 

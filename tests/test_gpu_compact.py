@@ -107,6 +107,15 @@ def test_compact_batch_widths(batch):
     plan.close()
 
 
+def test_compact_more_column_blocks_than_one_grid_holds():
+    """An odd batch takes one scalar column per workgroup row; 65 541 of them need two launches."""
+    shape, batch = (3, 4, 3, 1, 1), 65541
+    x, K = _rand(shape, batch, 17)
+    plan = build_plan_c(shape, K)
+    check_apply(plan, shape, K, x, batch)
+    plan.close()
+
+
 def test_compact_unaligned_operands_take_the_scalar_columns():
     shape, batch = (80, 300, 7, 1, 3), 4
     m, n, k, s, p = shape
