@@ -21,12 +21,14 @@
 //     the rectangle it describes, whatever it is (borders, any k and s, edited
 //     descriptors; a tap whose column is not on a resident line is read from
 //     global memory);
-//   - for common (k, s), compiled in: when every row a wave holds is described as
-//     a full k x k rectangle at the position the stride dictates (checked on the
-//     descriptors read, not assumed), a lane computes RV vertically adjacent
-//     outputs at once, so that a pixel read from LDS feeds the taps of up to RV
-//     rows, with the kernel numbers in scalar registers and the LDS offsets of a
-//     line's pixels as immediates.
+//   - the rectangle path, compiled in for common (k, s) at strides 1 and 2: the ring
+//     holds the zero-padded plane, so when every row a wave holds is described
+//     exactly as Theorem 2.1 says the window at its position must be (checked on
+//     the descriptors read, not assumed), the full k x k sum over the padded plane
+//     is the row's sum.  A lane then computes RV vertically adjacent outputs at
+//     once: a pixel read from LDS feeds the taps of up to RV rows, the kernel
+//     numbers sit in registers and the LDS offsets of a line's pixels are
+//     immediates.
 #pragma once
 #include <type_traits>
 

@@ -624,10 +624,18 @@ struct CompactChoice {
 };
 
 // rectangle path instantiations: s = 1 and these k, RV = 4 lines per lane, ring of 16
-constexpr int kRectRv = 4, kRectNl = 16, kRectXld = 5;
+// ring of 16 lines; 4 output lines per lane and step at stride 1, 2 at stride 2 (the ring must
+// hold s*(2*RV-1) + k lines); registers per thread for the next step's RV*s lines
+constexpr int kRectNl = 16;
+constexpr int rect_rv(int s) { return s == 1 ? 4 : 2; }
+constexpr int rect_xld(int k, int s, int lpr) {
+    return (rect_rv(s) * s * ((kCompactThreads / lpr - 1) * s + k) * lpr + kCompactThreads - 1) / kCompactThreads;
+}
 constexpr int kCompactTargetBlocks = 512;
 
-bool rect_compiled(int k, int s) { return s == 1 && (k == 3 || k == 5 || k == 7); }
+bool rect_compiled(int k, int s) {
+    return (s == 1 && (k == 3 || k == 5 || k == 7)) || (s == 2 && (k == 2 || k == 3 || k == 5 || k == 7));
+}
 
 CompactChoice choose_compact(const conv_plan *plan, const float *x, const float *y, int batch) {
     const ConvShape &sh = plan->shape;
@@ -648,11 +656,11 @@ CompactChoice choose_compact(const conv_plan *plan, const float *x, const float 
     const int kk_bytes = sh.k * sh.k * 4;
     // the rectangle path compares descriptors with (s*x - p)*n + s*y - p in int, for x up to m_out + RV
     // ... and addresses lanes by 32-bit offsets from a line's start: n*batch*4 < 2^24, TW*batch*4 < 2^32
-    if (rect_compiled(sh.k, sh.s) && ((int64_t)sh.m + sh.p + sh.k + (kRectRv + 1) * (int64_t)sh.s) * sh.n < kInt32Limit &&
+    if (rect_compiled(sh.k, sh.s) && ((int64_t)sh.m + sh.p + sh.k + (rect_rv(sh.s) + 1) * (int64_t)sh.s) * sh.n < kInt32Limit &&
         (int64_t)sh.n * batch * 4 < (1LL << 24) && (int64_t)batch * 4 * (kCompactThreads + 1) < (1LL << 31)) {
         c.kk = sh.k;
         c.ss = sh.s;
-        g.rv = kRectRv;
+        g.rv = rect_rv(sh.s);
         g.nl = kRectNl;
         g.ktab_lds = 1;
         c.lds = (size_t)kRectNl * iw * c.lpr * eb + kk_bytes;
@@ -698,7 +706,8 @@ CompactChoice choose_compact(const conv_plan *plan, const float *x, const float 
 template <int KK, int SS, int LPR, bool SCALAR>
 bool launch_compact_inst(const CompactChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
     constexpr bool FAST = KK > 0;
-    auto kern = spmm_compact_kernel<KK, SS, LPR, SCALAR, FAST ? kRectRv : 0, FAST ? kRectNl : 0, FAST ? kRectXld : 0>;
+    auto kern = spmm_compact_kernel<KK, SS, LPR, SCALAR, FAST ? rect_rv(SS) : 0, FAST ? kRectNl : 0,
+                                    FAST ? rect_xld(KK, SS, LPR) : 0>;
     static thread_local bool allowed[64];
     if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
     constexpr unsigned kMaxGridY = 65535;
@@ -713,6 +722,14 @@ bool launch_compact_inst(const CompactChoice &c, const conv_plan *plan, const fl
 
 template <int LPR, bool SCALAR>
 bool launch_compact_k(const CompactChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    if (c.ss == 2) {
+        switch (c.kk) {
+            case 2: return launch_compact_inst<2, 2, LPR, SCALAR>(c, plan, x, y, q);
+            case 3: return launch_compact_inst<3, 2, LPR, SCALAR>(c, plan, x, y, q);
+            case 5: return launch_compact_inst<5, 2, LPR, SCALAR>(c, plan, x, y, q);
+            default: return launch_compact_inst<7, 2, LPR, SCALAR>(c, plan, x, y, q);
+        }
+    }
     switch (c.kk) {
         case 3: return launch_compact_inst<3, 1, LPR, SCALAR>(c, plan, x, y, q);
         case 5: return launch_compact_inst<5, 1, LPR, SCALAR>(c, plan, x, y, q);

@@ -49,16 +49,21 @@ RECT = [   # (k, s) with a compiled rectangle path: several strips, segments, ra
     ((200, 257, 3, 1, 1), 1), ((70, 70, 7, 1, 3), 32), ((41, 600, 5, 1, 4), 4), ((9, 9, 7, 1, 3), 16),
     ((7, 300, 7, 1, 0), 8), ((300, 7, 7, 1, 0), 16), ((260, 130, 3, 1, 0), 12), ((33, 65, 7, 1, 5), 48),
 ]
+RECT_S2 = [   # stride 2: two output lines per lane and step
+    ((100, 90, 5, 2, 2), 16), ((224, 224, 7, 2, 3), 16), ((257, 513, 3, 2, 1), 1), ((300, 301, 2, 2, 0), 8),
+    ((3, 50, 7, 2, 3), 5), ((112, 112, 3, 2, 1), 4), ((131, 77, 7, 2, 0), 16), ((64, 300, 5, 2, 4), 2),
+    ((56, 56, 2, 2, 0), 32), ((40, 700, 3, 2, 2), 12), ((9, 9, 7, 2, 3), 16), ((515, 66, 2, 2, 1), 1),
+]
 DESCRIBED = [
-    ((100, 90, 5, 2, 2), 16), ((75, 75, 9, 3, 8), 4), ((90, 141, 11, 4, 5), 2), ((40, 40, 13, 1, 6), 3),
-    ((3, 50, 7, 2, 3), 5), ((6, 6, 2, 1, 5), 7), ((1, 1, 1, 5, 2), 3), ((200, 1, 1, 1, 0), 6),
-    ((300, 301, 2, 2, 0), 8), ((257, 513, 3, 2, 1), 1), ((64, 1000, 5, 3, 1), 4), ((224, 224, 7, 2, 3), 16),
+    ((100, 90, 5, 3, 2), 16), ((75, 75, 9, 3, 8), 4), ((90, 141, 11, 4, 5), 2), ((40, 40, 13, 1, 6), 3),
+    ((3, 50, 7, 5, 3), 5), ((6, 6, 2, 1, 5), 7), ((1, 1, 1, 5, 2), 3), ((200, 1, 1, 1, 0), 6),
+    ((300, 301, 2, 3, 0), 8), ((257, 513, 3, 4, 1), 1), ((64, 1000, 5, 3, 1), 4), ((224, 224, 7, 3, 3), 16),
     ((120, 120, 100, 5, 50), 4), ((260, 260, 255, 3, 0), 1), ((60, 70, 40, 1, 20), 16), ((500, 40, 4, 1, 2), 8),
     ((31, 31, 6, 1, 9), 16), ((150, 150, 1, 1, 0), 16), ((97, 400, 2, 1, 1), 4),
 ]
 
 
-@pytest.mark.parametrize("shape,batch", RECT + DESCRIBED)
+@pytest.mark.parametrize("shape,batch", RECT + RECT_S2 + DESCRIBED)
 def test_compact_shapes(shape, batch):
     x, K = _rand(shape, batch, 3)
     plan = build_plan_c(shape, K)
@@ -68,13 +73,14 @@ def test_compact_shapes(shape, batch):
 
 
 def test_rectangle_path_is_dispatched_where_compiled():
-    for shape, batch in RECT:
+    for shape, batch in RECT + RECT_S2:
         plan = build_plan_c(shape, np.ones(shape[2] ** 2, dtype=np.float32))
-        assert plan.variant(batch).startswith("compact_rect_k%ds1" % shape[2]), plan.variant(batch)
+        assert plan.variant(batch).startswith("compact_rect_k%ds%d" % (shape[2], shape[3])), plan.variant(batch)
         plan.close()
-    plan = build_plan_c((100, 90, 5, 2, 2), np.ones(25, dtype=np.float32))
-    assert plan.variant(16).startswith("compact_described"), plan.variant(16)
-    plan.close()
+    for shape, batch in DESCRIBED:
+        plan = build_plan_c(shape, np.ones(shape[2] ** 2, dtype=np.float32))
+        assert plan.variant(batch).startswith("compact_described"), (shape, plan.variant(batch))
+        plan.close()
 
 
 @pytest.mark.parametrize("shape", sorted(set(workloads.densenet121_layer_shapes())))
