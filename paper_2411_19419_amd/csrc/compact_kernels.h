@@ -70,7 +70,8 @@ __global__ void compact_table_kernel(const float *__restrict__ kernel, float *__
 struct CompactGeom {
     int m, n, m_out, n_out, s, p, k;
     int batch;            // x / y row pitch, in floats
-    int strips;           // strips of TW output columns
+    int tw;               // output columns per strip (rectangle kernels: 256 / lanes per row)
+    int strips;           // strips of tw output columns
     int seg;              // output lines per workgroup (a multiple of rv)
     int segs;             // segments per strip
     int blocks_per_xcd;
@@ -117,10 +118,16 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
     const int job = (blockIdx.x % kXcds) * g.blocks_per_xcd + local;
     if (local >= g.blocks_per_xcd || job >= g.strips * g.segs) return;      // uniform over the block
     const int sg = job / g.strips, tx = job - sg * g.strips;
-    const int y0 = tx * TW, xa = sg * g.seg, xb = min(xa + g.seg, g.m_out);
-    const int twc = min(TW, g.n_out - y0);
+    // Strip width: the rectangle kernels give every row of an output line to its own lanes; the
+    // described path may take narrower strips (the ring then fits LDS at large strides) and
+    // hands the lines of a step to the NT / (tw * LPR) groups of lanes in turn.
+    const int tw = FAST ? TW : g.tw;
+    const int y0 = tx * tw, xa = sg * g.seg, xb = min(xa + g.seg, g.m_out);
+    const int twc = min(tw, g.n_out - y0);
     const int c0 = g.c_base + blockIdx.y * NCOL;
-    const int tid = threadIdx.x, yy = tid / LPR, v = tid % LPR;
+    const int tid = threadIdx.x, v = tid % LPR;
+    const int line_lanes = tw * LPR, line_group = FAST ? 0 : tid / line_lanes, line_groups = FAST ? 1 : NT / line_lanes;
+    const int yy = (FAST ? tid : tid - line_group * line_lanes) / LPR;
 
     // ---- the ring holds the zero-padded plane: line i (any sign) in slot i mod NL, pixels
     // j_lo .. j_lo + iw - 1 of it, zeros wherever (i, j) is not a pixel of the image
@@ -348,7 +355,7 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
             }
         } else {
             if (yy < twc)
-                for (int j = 0; j < rv && xo + j < xb; ++j)
+                for (int j = line_group; j < rv && xo + j < xb; j += line_groups)
                     row_described(xo + j, desc[(long long)(xo + j) * g.n_out + (y0 + yy)], lo_step, hi_step);
         }
     };

@@ -645,14 +645,13 @@ CompactChoice choose_compact(const conv_plan *plan, const float *x, const float 
     c.lpr = c.scalar ? 1 : (batch % 16 == 0 ? 4 : (batch % 8 == 0 ? 2 : 1));
     const int ncol = c.scalar ? 1 : 4 * c.lpr, eb = c.scalar ? 4 : 16;
     c.col_blocks = (unsigned)(batch / ncol);
-    const int tw = kCompactThreads / c.lpr;
+    int tw = kCompactThreads / c.lpr;
     CompactGeom g{};
     g.m = sh.m; g.n = sh.n; g.m_out = sh.m_out; g.n_out = sh.n_out; g.s = sh.s; g.p = sh.p; g.k = sh.k;
     g.batch = batch;
     // int arithmetic in the kernel: s*x - p + k, s*y0 - p + iw
-    const int64_t iw = (int64_t)(tw - 1) * sh.s + sh.k;
+    int64_t iw = (int64_t)(tw - 1) * sh.s + sh.k;
     if ((int64_t)sh.m + 2LL * sh.p + sh.k >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + iw >= (1LL << 30)) return c;
-    g.iw = (int)iw;
     const int kk_bytes = sh.k * sh.k * 4;
     // the rectangle path compares descriptors with (s*x - p)*n + s*y - p in int, for x up to m_out + RV
     // ... and addresses lanes by 32-bit offsets from a line's start: n*batch*4 < 2^24, TW*batch*4 < 2^32
@@ -665,28 +664,40 @@ CompactChoice choose_compact(const conv_plan *plan, const float *x, const float 
         g.ktab_lds = 1;
         c.lds = (size_t)kRectNl * iw * c.lpr * eb + kk_bytes;
     } else {
-        // described path: the most lines per step whose ring fits 64 KiB (two barriers per
-        // step, so the ring holds one step's lines), else one line per step in up to 144 KiB;
-        // none fits: every tap from global memory
+        // Described path.  A strip of tw columns is served by 256 / (tw * lpr) groups of lanes that
+        // take the rv lines of a step in turn (rv = 4, 2 or 1 lines per group); two barriers per
+        // step, so the ring holds one step's s*(rv-1) + k lines of (tw-1)*s + k pixels.  Widest
+        // strip (not wider than the image needs) and most lines whose ring fits 64 KiB, else
+        // 144 KiB (one workgroup per CU); none fits: every tap from global memory.
         g.ktab_lds = kk_bytes <= 16 * 1024;
         g.rv = 1;
         g.nl = 0;
         c.lds = g.ktab_lds ? kk_bytes : 0;
-        const int rvs[4] = {4, 2, 1, 1};
-        for (int t = 0; t < 4; ++t) {
-            const int rv = rvs[t];
-            const int64_t limit = t < 3 ? 64 * 1024 : 144 * 1024;
-            const int64_t need = (int64_t)sh.s * (rv - 1) + sh.k;
-            int nl = 16;
-            while (nl < need && nl < 256) nl <<= 1;
-            const int64_t bytes = (int64_t)nl * iw * c.lpr * eb + (g.ktab_lds ? kk_bytes : 0);
-            if (nl < need || bytes > limit || (int64_t)nl * iw * c.lpr >= (1LL << 21)) continue;
-            g.rv = rv;
-            g.nl = nl;
-            c.lds = (size_t)bytes;
-            break;
+        const int64_t limits[2] = {64 * 1024, 144 * 1024};
+        bool found = false;
+        for (int li = 0; li < 2 && !found; ++li) {
+            for (int cand = kCompactThreads / c.lpr; cand >= 16 && !found; cand >>= 1) {
+                if (cand > 16 && cand / 2 >= sh.n_out) continue;      // half as wide still covers the image
+                for (int mult = 4; mult >= 1 && !found; mult >>= 1) {
+                    const int rv = kCompactThreads / (cand * c.lpr) * mult;
+                    const int64_t cw = (int64_t)(cand - 1) * sh.s + sh.k;
+                    const int64_t need = (int64_t)sh.s * (rv - 1) + sh.k;
+                    int nl = 16;
+                    while (nl < need && nl < 256) nl <<= 1;
+                    const int64_t bytes = (int64_t)nl * cw * c.lpr * eb + (g.ktab_lds ? kk_bytes : 0);
+                    if (nl < need || bytes > limits[li] || (int64_t)nl * cw * c.lpr >= (1LL << 21)) continue;
+                    tw = cand;
+                    iw = cw;
+                    g.rv = rv;
+                    g.nl = nl;
+                    c.lds = (size_t)bytes;
+                    found = true;
+                }
+            }
         }
     }
+    g.tw = tw;
+    g.iw = (int)iw;
     g.strips = (sh.n_out + tw - 1) / tw;
     int64_t segs = kCompactTargetBlocks / ((int64_t)g.strips * c.col_blocks);
     if (segs < 1) segs = 1;
@@ -911,9 +922,9 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch) {
         else snprintf(cols, sizeof cols, "float4x%d", cc.lpr);
         if (cc.kk)
             snprintf(name, sizeof name, "compact_rect_k%ds%d_%dx%d_ring%d_rv%d_%s", cc.kk, cc.ss, cc.geom.seg,
-                     kCompactThreads / cc.lpr, cc.geom.nl, cc.geom.rv, cols);
+                     cc.geom.tw, cc.geom.nl, cc.geom.rv, cols);
         else
-            snprintf(name, sizeof name, "compact_described_%dx%d_ring%d_rv%d_%s", cc.geom.seg, kCompactThreads / cc.lpr,
+            snprintf(name, sizeof name, "compact_described_%dx%d_ring%d_rv%d_%s", cc.geom.seg, cc.geom.tw,
                      cc.geom.nl, cc.geom.rv, cols);
         return name;
     }
