@@ -142,3 +142,26 @@ def test_workload_generators_are_seeded_and_shaped():
     k = workloads.make_kernel(w.k, w.k_std, w.seed)
     assert abs(float(np.std(k)) - 1.0 / 7.0) < 0.05
     assert len(workloads.densenet121_layer_shapes()) == 123
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/convspmv.h is a C header: it compiles as C99 with gcc, alone, and a C program that
+    calls the host-only entry points through it links against the library and runs."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "use_header.c"
+    src.write_text(
+        '#include "convspmv.h"\n'
+        '#include <stdio.h>\n'
+        'int main(void) {\n'
+        '    int mo = 0, no = 0;\n'
+        '    if (conv_out_shape(1024, 1024, 7, 1, 3, &mo, &no) != CONV_OK) return 1;\n'
+        '    printf("%d %d %lld %s\\n", mo, no, (long long)conv_nnz(1024, 1024, 7, 1, 3), conv_strerror(CONV_EALIAS));\n'
+        '    return conv_nnz(4, 4, 9, 1, 0) == CONV_EINVAL ? 0 : 2;\n'
+        '}\n')
+    exe = tmp_path / "use_header"
+    libdir = os.path.dirname(binding.library_path())
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                    str(src), "-o", str(exe), "-L", libdir, "-lconvspmv", "-Wl,-rpath," + libdir], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(None, 3)
+    assert out[:3] == ["1024", "1024", "51208336"] and out[3].strip() == "x and y overlap"
