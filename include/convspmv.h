@@ -163,6 +163,17 @@ int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream);
  * order.)  x and y must not overlap. */
 int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch, void *stream);
 
+/* y = T x computed from the column-compressed arrays, as the paper's CSC
+ * variants do (Sections 3 and 4.1: the same T stored by columns).  `plan` must
+ * come from conv_csc_build (CONV_EINVAL otherwise); x_dev has m*n*batch
+ * elements, y_dev m_out*n_out*batch, both batch-minor.  By columns the product
+ * is a scatter: y is zeroed, then every stored entry adds vals[e]*x[column] to
+ * y[row_idx[e]] with one hardware float add.  The result is that of conv_spmv
+ * on the CSR plan of the same T up to the order of the additions, which here
+ * depends on timing: repeated calls agree to rounding, not bit for bit.  The
+ * arrays are read as stored (every row_idx must be in [0, m_out*n_out)). */
+int conv_spmv_from_csc(const conv_plan *plan, const float *x_dev, float *y_dev, int batch, void *stream);
+
 /* Shape and size queries on a plan (host only).  conv_plan_is_transposed
  * returns 1 for a plan made by conv_csc_build, conv_plan_is_compact 1 for a
  * plan made by conv_compact_build, 0 otherwise, < 0 on error. */

@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     conv_out_shape,
     conv_set_march_min_jobs,
     conv_spmv,
+    conv_spmv_from_csc,
     conv_strerror,
     conv_update_kernel,
     library_path,

@@ -23,7 +23,7 @@ EXPORTS = (
     "conv_multi_create", "conv_multi_apply", "conv_multi_destroy",
     "conv_csc_build", "conv_plan_is_transposed",
     "conv_compact_build", "conv_plan_is_compact",
-    "conv_csr_build_channels", "conv_plan_channels",
+    "conv_csr_build_channels", "conv_plan_channels", "conv_spmv_from_csc",
 )
 
 
@@ -68,6 +68,8 @@ def _load():
         lib.conv_csr_build_channels.restype = i
         lib.conv_plan_channels.argtypes = [vp]
         lib.conv_plan_channels.restype = i
+        lib.conv_spmv_from_csc.argtypes = [vp, vp, vp, i, vp]
+        lib.conv_spmv_from_csc.restype = i
         lib.conv_spmv.argtypes = [vp, vp, vp, i, vp]
         lib.conv_spmv.restype = i
         lib.conv_plan_shape.argtypes = [vp, pi, pi, pi, pi, pi, pi, pi, pi64]
@@ -305,6 +307,26 @@ def conv_spmv(plan: ConvPlan, x, y=None, batch: int = 1, stream=None):
             st = _load().conv_spmv(plan._handle, x.data_ptr(), y.data_ptr(), int(batch), sh)
     if st != 0:
         raise ConvError(st, "conv_spmv(batch=%d)" % batch)
+    return y
+
+
+def conv_spmv_from_csc(plan: ConvPlan, x, y=None, batch: int = 1, stream=None):
+    """y = T x from the column-compressed arrays of a conv_csc_build plan (a scatter)."""
+    import torch
+    if plan._handle is None:
+        raise ValueError("plan is closed")
+    if not (x.is_cuda and x.dtype == torch.float32 and x.is_contiguous() and x.numel() == plan.m * plan.n * batch):
+        raise ValueError("x must be a contiguous float32 device tensor with m*n*batch elements")
+    out = plan.m_out * plan.n_out * batch
+    if y is None:
+        y = torch.empty(out, dtype=torch.float32, device=x.device)
+    elif not (y.is_cuda and y.dtype == torch.float32 and y.is_contiguous() and y.numel() == out):
+        raise ValueError("y must be a contiguous float32 device tensor with m_out*n_out*batch elements")
+    with torch.cuda.device(x.device):
+        sh, _ = _stream_handle(stream)
+        st = _load().conv_spmv_from_csc(plan._handle, x.data_ptr(), y.data_ptr(), int(batch), sh)
+    if st != 0:
+        raise ConvError(st, "conv_spmv_from_csc(batch=%d)" % batch)
     return y
 
 

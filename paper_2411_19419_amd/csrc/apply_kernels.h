@@ -119,6 +119,35 @@ __global__ __launch_bounds__(kGatherThreads) void spmm_gather_vec_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// y = T x from the column-compressed arrays of T (the paper's CSC variants, Sections 3 and
+// 4.1, multiply by the same T stored by columns).  By columns the product is a scatter:
+// column j contributes vals[e] * x[j] to row row_idx[e].  G lanes share a column; each
+// contribution is one hardware float add to y (zeroed beforehand by fill_zero_kernel), so
+// the summation order, unlike everywhere else in this library, depends on timing.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kGatherThreads) void fill_zero_kernel(float *__restrict__ y, long long count) {
+    const long long stride = (long long)gridDim.x * kGatherThreads;
+    for (long long i = (long long)blockIdx.x * kGatherThreads + threadIdx.x; i < count; i += stride) y[i] = 0.0f;
+}
+
+// BL consecutive lanes take BL neighbouring batch columns of one entry, so that their adds fall
+// into one 64-byte line of y and travel to the L2 as one request.
+template <int G, int BL>
+__global__ __launch_bounds__(kGatherThreads) void spmm_scatter_kernel(
+    const int *__restrict__ col_ptr, const int *__restrict__ row_idx, const float *__restrict__ vals,
+    const float *__restrict__ x, float *__restrict__ y, int cols, int batch) {
+    const long long col = ((long long)blockIdx.x * kGatherThreads + threadIdx.x) / (G * BL);
+    const int r = (int)threadIdx.x % (G * BL), lane = r / BL, bl = r % BL;
+    if (col >= cols) return;
+    const int beg = col_ptr[col], end = col_ptr[col + 1];
+    for (int c = blockIdx.y * BL + bl; c < batch; c += gridDim.y * BL) {
+        const float xv = x[col * batch + c];
+        for (int e = beg + lane; e < end; e += G)
+            unsafeAtomicAdd(y + (long long)row_idx[e] * batch + c, vals[e] * xv);
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Many small products in one launch.  The paper's experiment (Section 4.1)
 // applies 123 small, independent transformations (the DenseNet121 layer shapes
 // of Table 2, 7x7 ... 224x224 pixels); each of them is a few microseconds of

@@ -805,6 +805,49 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
     return CONV_OK;
 }
 
+int conv_spmv_from_csc(const conv_plan *plan, const float *x_dev, float *y_dev, int batch, void *stream) {
+    if (!plan || !x_dev || !y_dev) return CONV_ENULL;
+    if (batch < 1 || !plan->transposed || plan->compact) return CONV_EINVAL;
+    // the plan's "rows" are the columns of T (input pixels), its "cols" the rows of T
+    const int64_t in_pixels = plan->rows, out_pixels = plan->cols;
+    {
+        const char *xb = (const char *)x_dev, *xe = xb + sizeof(float) * (size_t)in_pixels * batch;
+        const char *yb = (const char *)y_dev, *ye = yb + sizeof(float) * (size_t)out_pixels * batch;
+        if (xb < ye && yb < xe) return CONV_EALIAS;
+    }
+    hipStream_t q = (hipStream_t)stream;
+    const long long count = (long long)out_pixels * batch;
+    const unsigned fill_blocks = (unsigned)std::min<long long>((count + kGatherThreads - 1) / kGatherThreads, 1 << 16);
+    fill_zero_kernel<<<fill_blocks, kGatherThreads, 0, q>>>(y_dev, count);
+    if (plan->nnz > 0) {
+        const int g = group_width(plan->max_row_nnz);
+        const int bl = batch >= 16 ? 16 : (batch >= 4 ? 4 : 1);      // lanes across the batch
+        const int64_t blocks = (in_pixels * g * bl + kGatherThreads - 1) / kGatherThreads;
+        if (blocks > kInt32Limit) return CONV_EOVERFLOW;
+        const unsigned bx = (unsigned)blocks;
+        const unsigned by = (unsigned)std::min((batch + bl - 1) / bl, 65535);
+        const dim3 grid(bx, by);
+        const int cols = (int)in_pixels;
+#define CONV_SCATTER_BL(G, BL)                                                                              \
+    spmm_scatter_kernel<G, BL><<<grid, kGatherThreads, 0, q>>>(plan->row_ptr, plan->col_idx, plan->vals, x_dev, \
+                                                               y_dev, cols, batch)
+#define CONV_SCATTER(G)                                  \
+    if (bl == 16) CONV_SCATTER_BL(G, 16);                \
+    else if (bl == 4) CONV_SCATTER_BL(G, 4);             \
+    else CONV_SCATTER_BL(G, 1)
+        switch (g) {
+            case 1: CONV_SCATTER(1); break;
+            case 2: CONV_SCATTER(2); break;
+            case 4: CONV_SCATTER(4); break;
+            case 8: CONV_SCATTER(8); break;
+            default: CONV_SCATTER(16); break;
+        }
+#undef CONV_SCATTER_BL
+#undef CONV_SCATTER
+    }
+    return hip_ok(hipGetLastError()) ? CONV_OK : CONV_EHIP;
+}
+
 // ---------------------------------------------------------------------------
 // Many small products in one launch
 // ---------------------------------------------------------------------------

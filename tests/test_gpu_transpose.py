@@ -186,3 +186,49 @@ def test_transposed_march_reads_the_stored_arrays(march_everywhere):
     scale = (np.abs(va[seg]).astype(np.float64)[:, None] * np.abs(U[ri2[seg]])).sum(axis=0)
     assert np.all(np.abs(z1h[row] - want) <= 1e-5 * scale)
     plan.close()
+
+
+@pytest.mark.parametrize("shape,batch", [
+    ((37, 53, 7, 1, 3), 16), ((130, 67, 7, 1, 3), 4), ((100, 90, 5, 2, 2), 8), ((33, 200, 3, 1, 1), 1),
+    ((75, 75, 9, 3, 8), 3), ((40, 40, 13, 1, 6), 5), ((6, 6, 2, 1, 5), 7), ((1, 1, 1, 5, 2), 3),
+    ((224, 224, 7, 2, 3), 16), ((5, 5, 2, 2, 0), 4), ((300, 301, 2, 2, 0), 12),
+])
+def test_product_from_the_csc_arrays_is_the_convolution(shape, batch):
+    """y = T x computed by scattering the column-compressed entries (the paper's CSC variant)
+    against the sliding-window oracle.  The additions happen in a timing-dependent order, so two
+    runs are compared with each other to the same tolerance, not bit for bit."""
+    m, n, k, s, p = shape
+    rng = np.random.default_rng(13)
+    x = rng.standard_normal(m * n * batch).astype(np.float32)
+    K = rng.standard_normal(k * k).astype(np.float32)
+    plan = build_plan_t(shape, K)
+    xd = torch.from_numpy(x).to(device())
+    y = torch.full((plan.cols * batch,), float("nan"), dtype=torch.float32, device=device())
+    cs.conv_spmv_from_csc(plan, xd, y, batch=batch)
+    y2 = cs.conv_spmv_from_csc(plan, xd, batch=batch)
+    torch.cuda.synchronize()
+    ref, scale = oracle.conv(m, n, k, s, p, x, K, batch=batch, want_scale=True)
+    for got in (y.cpu().numpy(), y2.cpu().numpy()):
+        assert not np.any(np.isnan(got))
+        live = scale > 0
+        assert np.all(got[~live] == 0.0)
+        err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+        assert (np.max(err[live] / scale[live]) if np.any(live) else 0.0) <= 1e-5
+    plan.close()
+
+
+def test_product_from_csc_needs_a_csc_plan():
+    shape = (8, 8, 3, 1, 1)
+    K = np.ones(9, dtype=np.float32)
+    plan = build_plan(shape, K)
+    x = torch.zeros(64, device=device())
+    with pytest.raises(cs.ConvError) as e:
+        cs.conv_spmv_from_csc(plan, x, batch=1)
+    assert e.value.status == -1
+    plan.close()
+    pt = build_plan_t(shape, K)
+    with pytest.raises(cs.ConvError) as e:          # x and y overlap
+        buf = torch.zeros(128, device=device())
+        cs.conv_spmv_from_csc(pt, buf[:64], buf[32:96], batch=1)
+    assert e.value.status == -6
+    pt.close()
