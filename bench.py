@@ -199,6 +199,8 @@ def main():
     ap.add_argument("--compact", action="store_true",
                     help="build T in the structure-aware storage (row descriptors + k*k table) and time y = T x from it")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--no-side-paths", action="store_true",
+                    help="skip the brief timing of the structure-aware storage and of T^T on the same workload")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this path is built and timed on a single MI355X "
@@ -355,6 +357,30 @@ def main():
                                 "frac": tflops / FP32_VECTOR_PEAK_TFLOPS,
                                 "frac_of_unpacked_fp32_peak": tflops / FP32_UNPACKED_PEAK_TFLOPS,
                                 "hbm_frac": achieved / HBM_PEAK_GBS})
+    if not (args.compact or args.transposed) and not args.no_side_paths:
+        # the widened paths on the same workload, briefly (outside the timed region above): HIP-event
+        # average of single launches after a warm-up; their own runs are --compact and --transposed
+        side = {}
+        for tag, build in (("compact_storage", cs.conv_compact_build), ("transposed_csc", cs.conv_csc_build)):
+            pl = build(m, n, k, s, p, K)
+            xin = x if tag == "compact_storage" else torch.empty(pl.cols * w.batch, dtype=torch.float32,
+                                                                  device=dev).normal_()
+            yo = torch.empty(pl.rows * w.batch, dtype=torch.float32, device=dev)
+            for _ in range(100):
+                cs.conv_spmv(pl, xin, yo, batch=w.batch)
+            torch.cuda.synchronize()
+            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
+            for a, b in pairs:
+                a.record(stream)
+                cs.conv_spmv(pl, xin, yo, batch=w.batch)
+                b.record(stream)
+            torch.cuda.synchronize()
+            avg = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
+            side[tag] = {"kernel": pl.variant(w.batch), "kernel_ms_avg": avg, "model_bytes": pl.model_bytes(w.batch),
+                         "model_gbs": pl.model_bytes(w.batch) / (avg * 1e-3) / 1e9,
+                         "useful_tflops": 2.0 * pl.nnz * w.batch / (avg * 1e-3) / 1e12}
+            pl.close()
+        out["side_paths"] = side
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, x_h, K_h, args.transposed)
         out["gpu_over_cpu"] = out["useful_mac_per_s"] / 1e9 / out["cpu_baseline"]["value"]
