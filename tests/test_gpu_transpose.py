@@ -232,3 +232,53 @@ def test_product_from_csc_needs_a_csc_plan():
         cs.conv_spmv_from_csc(pt, buf[:64], buf[32:96], batch=1)
     assert e.value.status == -6
     pt.close()
+
+
+def test_largest_index_range_transposed():
+    """The column-compressed build and z = T^T u with nnz just below 2^31 (6600 x 6600, k = 7,
+    'same' padding): col_ptr in full against the prefix sums of the window counts, row_idx /
+    vals on sampled columns against the windows that cover the pixel (Section 2: tap
+    (i+p-s x, j+p-s y) of window (x, y)), z in full against the scatter-and-crop oracle."""
+    shape, batch = (6600, 6600, 7, 1, 3), 1
+    m, n, k, s, p = shape
+    mo, no = oracle.out_shape(*shape)
+    nnz = oracle.nnz_closed(*shape)
+    rng = np.random.default_rng(32)
+    u = rng.standard_normal(mo * no * batch).astype(np.float32)
+    K = rng.standard_normal(k * k).astype(np.float32)
+    plan = build_plan_t(shape, K)
+    assert plan.nnz == nnz
+
+    def cover(t, count_out):      # windows x in [0, count_out) with 0 <= t + p - s x < k
+        xs = np.arange(count_out, dtype=np.int64)
+        return np.array([np.count_nonzero((ti + p - s * xs >= 0) & (ti + p - s * xs < k)) for ti in t], dtype=np.int64)
+
+    # s = 1 here: q(t) = number of x in [max(0, t+p-k+1), min(count_out-1, t+p)]
+    t1, t2 = np.arange(m, dtype=np.int64), np.arange(n, dtype=np.int64)
+    q1 = np.minimum(mo - 1, t1 + p) - np.maximum(0, t1 + p - k + 1) + 1
+    q2 = np.minimum(no - 1, t2 + p) - np.maximum(0, t2 + p - k + 1) + 1
+    assert np.array_equal(q1[:20], cover(t1[:20], mo)) and np.array_equal(q1[-20:], cover(t1[-20:], mo))
+    want = np.concatenate([[0], np.cumsum(np.outer(q1, q2).reshape(-1))])
+    assert want[-1] == nnz
+    got_cp = plan.row_ptr.cpu().numpy()
+    assert np.array_equal(got_cp.astype(np.int64), want)
+    del want
+    K2 = K.reshape(k, k)
+    cols = np.unique(np.concatenate([np.arange(150), np.arange(m * n - 150, m * n), rng.integers(0, m * n, size=2000)]))
+    for c in cols:
+        i, j = divmod(int(c), n)
+        rows, vals = [], []
+        for x in range(max(0, i + p - k + 1), min(mo - 1, i + p) + 1):
+            for y in range(max(0, j + p - k + 1), min(no - 1, j + p) + 1):
+                rows.append(x * no + y)
+                vals.append(K2[i + p - x, j + p - y])
+        lo, hi = int(got_cp[c]), int(got_cp[c + 1])
+        assert plan.col_idx[lo:hi].cpu().numpy().astype(np.int64).tolist() == rows, c
+        assert np.array_equal(plan.vals[lo:hi].cpu().numpy().view(np.uint32), np.array(vals, dtype=np.float32).view(np.uint32)), c
+    z = cs.conv_spmv(plan, torch.from_numpy(u).to(device()), batch=batch)
+    torch.cuda.synchronize()
+    ref, scale = oracle.conv_t(m, n, k, s, p, u, K, batch=batch, want_scale=True)
+    got = z.cpu().numpy()
+    assert np.max(np.abs(got.astype(np.float64) - ref) / scale) <= 1e-5
+    print("largest transposed: variant %s" % plan.variant(batch))
+    plan.close()
