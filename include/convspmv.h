@@ -189,6 +189,29 @@ int conv_plan_channels(const conv_plan *plan);      /* input channels (1 unless 
  * thread. */
 const char *conv_spmv_variant(const conv_plan *plan, int batch);
 
+/* What conv_spmv would launch for a shape, without a plan and without a GPU
+ * (host only; 16-byte-aligned operands assumed): the kernel family and the
+ * launch geometry the dispatch derives.  storage: 0 = CSR of T, 1 = CSC of T
+ * (the plan applies T^T), 2 = structure-aware storage; channels > 1 only with
+ * storage 0.  Status as for the build calls (CONV_EINVAL, CONV_EOVERFLOW,
+ * CONV_ENULL).  For tests of the host logic and for reports. */
+typedef struct conv_dispatch {
+    int kernel;             /* 0 row-group scalar, 1 row-group float4, 2 LDS tile, 3 LDS march,
+                               4 described rows (structure-aware), 5 rectangle path (structure-aware) */
+    int threads;            /* per workgroup */
+    int64_t lds_bytes;      /* dynamic LDS per workgroup */
+    int64_t workgroups;     /* that do work, over the whole launch (per channel for kernel 3) */
+    int strip;              /* output columns per strip / tile line (kernels 2-5), else 0 */
+    int segment;            /* output lines per workgroup (kernels 2-5), else 0 */
+    int ring_lines;         /* LDS ring lines (kernels 3-5; 0 = no ring) */
+    int ring_lines_needed;  /* lines a step keeps resident (<= ring_lines when there is a ring) */
+    int lines_per_step;     /* output lines per step (kernels 3-5) */
+    int lanes_per_row;      /* lanes that share a row of the matrix */
+    int columns_per_lane;   /* batch columns per lane */
+} conv_dispatch;
+int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage, int channels,
+                       conv_dispatch *out);
+
 /* Release the host object and the plan-owned device table.  The caller must
  * have synchronised every stream the plan was used on.  NULL is accepted. */
 int conv_plan_destroy(conv_plan *plan);

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     conv_csc_build,
     conv_compact_build,
     conv_csr_build,
+    conv_dispatch_info,
     conv_csr_build_channels,
     conv_nnz,
     conv_out_shape,

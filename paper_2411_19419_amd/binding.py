@@ -23,8 +23,16 @@ EXPORTS = (
     "conv_multi_create", "conv_multi_apply", "conv_multi_destroy",
     "conv_csc_build", "conv_plan_is_transposed",
     "conv_compact_build", "conv_plan_is_compact",
-    "conv_csr_build_channels", "conv_plan_channels", "conv_spmv_from_csc",
+    "conv_csr_build_channels", "conv_plan_channels", "conv_spmv_from_csc", "conv_dispatch_info",
 )
+
+
+class ConvDispatch(ctypes.Structure):
+    """conv_dispatch of include/convspmv.h."""
+    _fields_ = [("kernel", ctypes.c_int), ("threads", ctypes.c_int), ("lds_bytes", ctypes.c_int64),
+                ("workgroups", ctypes.c_int64), ("strip", ctypes.c_int), ("segment", ctypes.c_int),
+                ("ring_lines", ctypes.c_int), ("ring_lines_needed", ctypes.c_int), ("lines_per_step", ctypes.c_int),
+                ("lanes_per_row", ctypes.c_int), ("columns_per_lane", ctypes.c_int)]
 
 
 class ConvError(RuntimeError):
@@ -70,6 +78,8 @@ def _load():
         lib.conv_plan_channels.restype = i
         lib.conv_spmv_from_csc.argtypes = [vp, vp, vp, i, vp]
         lib.conv_spmv_from_csc.restype = i
+        lib.conv_dispatch_info.argtypes = [i] * 8 + [ctypes.POINTER(ConvDispatch)]
+        lib.conv_dispatch_info.restype = i
         lib.conv_spmv.argtypes = [vp, vp, vp, i, vp]
         lib.conv_spmv.restype = i
         lib.conv_plan_shape.argtypes = [vp, pi, pi, pi, pi, pi, pi, pi, pi64]
@@ -107,6 +117,15 @@ def conv_set_march_min_jobs(jobs: int) -> int:
     if prev < 0:
         raise ConvError(prev, "conv_set_march_min_jobs(%r)" % (jobs,))
     return prev
+
+
+def conv_dispatch_info(m, n, k, s, p, batch=1, storage=0, channels=1) -> ConvDispatch:
+    """What conv_spmv would launch for this shape (host only, no GPU needed)."""
+    d = ConvDispatch()
+    st = _load().conv_dispatch_info(m, n, k, s, p, int(batch), int(storage), int(channels), ctypes.byref(d))
+    if st != 0:
+        raise ConvError(st, "conv_dispatch_info%r" % ((m, n, k, s, p, batch, storage, channels),))
+    return d
 
 
 def conv_out_shape(m, n, k, s, p):

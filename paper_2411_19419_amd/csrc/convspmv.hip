@@ -954,6 +954,68 @@ int conv_plan_is_transposed(const conv_plan *plan) { return plan ? (plan->transp
 int conv_plan_is_compact(const conv_plan *plan) { return plan ? (plan->compact ? 1 : 0) : CONV_ENULL; }
 int conv_plan_channels(const conv_plan *plan) { return plan ? plan->channels : CONV_ENULL; }
 
+int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage, int channels, conv_dispatch *out) {
+    if (!out) return CONV_ENULL;
+    int64_t mo, no;
+    const int st = check_shape(m, n, k, s, p, &mo, &no);
+    if (st != CONV_OK) return st;
+    if (batch < 1 || channels < 1 || storage < 0 || storage > 2 || (storage != 0 && channels != 1)) return CONV_EINVAL;
+    if (storage == 2 && k > 255) return CONV_EINVAL;
+    const int64_t nnz = conv_nnz(m, n, k, s, p);
+    if (nnz > kInt32Limit || mo * no >= kInt32Limit || (int64_t)m * n * channels >= kInt32Limit) return CONV_EOVERFLOW;
+    // a plan without arrays: the dispatch looks at the shape, the storage and operand alignment only
+    conv_plan plan{};
+    plan.shape = ConvShape{m, n, k, s, p, (int)mo, (int)no};
+    plan.transposed = storage == 1;
+    plan.compact = storage == 2;
+    plan.channels = channels;
+    plan.rows = plan.transposed ? (int64_t)m * n : mo * no;
+    plan.cols = plan.transposed ? mo * no : (int64_t)m * n * channels;
+    plan.nnz = nnz;
+    const int per_axis = plan.transposed ? (k + s - 1) / s : k;
+    plan.max_row_nnz = per_axis * per_axis;
+    conv_dispatch d{};
+    if (plan.compact) {
+        const CompactChoice cc = choose_compact(&plan, nullptr, nullptr, batch);
+        if (!cc.ok) return CONV_EOVERFLOW;
+        d.kernel = cc.kk ? 5 : 4;
+        d.threads = kCompactThreads;
+        d.lds_bytes = (int64_t)cc.lds;
+        d.strip = cc.geom.tw;
+        d.segment = cc.geom.seg;
+        d.ring_lines = cc.geom.nl;
+        d.lines_per_step = cc.geom.rv;
+        d.lanes_per_row = cc.lpr;
+        d.columns_per_lane = cc.scalar ? 1 : 4;
+        d.ring_lines_needed = cc.kk ? s * (2 * cc.geom.rv - 1) + k : (cc.geom.nl ? s * (cc.geom.rv - 1) + k : 0);
+        d.workgroups = (int64_t)cc.geom.strips * cc.geom.segs * cc.col_blocks;
+    } else {
+        const ApplyChoice c = choose_apply(&plan, nullptr, nullptr, batch);
+        d.kernel = c.kind == Kind::GatherScalar ? 0 : c.kind == Kind::GatherVec ? 1 : c.kind == Kind::Tile ? 2 : 3;
+        d.threads = c.threads;
+        d.lds_bytes = (int64_t)c.lds;
+        d.lanes_per_row = c.g;
+        d.columns_per_lane = c.nv ? 4 * c.nv : 1;
+        if (c.kind == Kind::March) {
+            const bool tr = plan.transposed;
+            d.strip = c.tw;
+            d.segment = c.march.seg;
+            d.ring_lines = c.nl;
+            d.lines_per_step = c.ls;
+            d.ring_lines_needed = tr ? (c.ls == 2 ? (k + 2) / s + 2 : k / s + 2) : s * (2 * c.ls - 1) + k;
+            d.workgroups = (int64_t)c.march.strips * c.march.segs * (c.nv ? batch / (4 * c.nv) : batch);
+        } else if (c.kind == Kind::Tile) {
+            d.strip = c.tw;
+            d.segment = c.geom.th;
+            d.workgroups = (int64_t)c.geom.n_tiles * (batch / (4 * c.nv));
+        } else {
+            d.workgroups = (plan.rows * c.g + kGatherThreads - 1) / kGatherThreads;
+        }
+    }
+    *out = d;
+    return CONV_OK;
+}
+
 const char *conv_spmv_variant(const conv_plan *plan, int batch) {
     if (!plan || batch < 1) return nullptr;
     static thread_local char name[96];

@@ -166,3 +166,76 @@ def test_header_is_plain_c(tmp_path):
                     str(src), "-o", str(exe), "-L", libdir, "-lconvspmv", "-Wl,-rpath," + libdir], check=True)
     out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(None, 3)
     assert out[:3] == ["1024", "1024", "51208336"] and out[3].strip() == "x and y overlap"
+
+
+def _dispatch(m, n, k, s, p, batch, storage=0, channels=1):
+    d = cs.conv_dispatch_info(m, n, k, s, p, batch, storage, channels)
+    return {f[0]: getattr(d, f[0]) for f in d._fields_}
+
+
+def test_dispatch_geometry_is_consistent_over_many_shapes():
+    """The host logic that picks a kernel and its launch geometry, queried without a GPU: LDS
+    within a CU's 160 KiB, rings at least as long as a step needs, strips and lanes that tile
+    the workgroup, on a grid of shapes, batches and storages."""
+    rng = np.random.default_rng(0)
+    shapes = [(1024, 1024, 7, 1, 3), (224, 224, 7, 2, 3), (4096, 4096, 11, 4, 5), (512, 512, 9, 3, 8),
+              (6600, 6600, 7, 1, 3), (20000, 300, 5, 1, 2), (300, 20000, 5, 2, 2), (64, 64, 1, 1, 0),
+              (300, 300, 255, 3, 100), (700, 900, 40, 1, 20), (56, 56, 2, 2, 0), (3, 3, 9, 2, 3)]
+    for _ in range(400):
+        k = int(rng.integers(1, 20))
+        s = int(rng.integers(1, 6))
+        p = int(rng.integers(0, 12))
+        m, n = (int(v) for v in rng.integers(max(1, k - 2 * p), 3000, size=2))
+        shapes.append((m, n, k, s, p))
+    seen = set()
+    for shape in shapes:
+        m, n, k, s, p = shape
+        for batch in (1, 3, 4, 8, 16, 64):
+            for storage in (0, 1, 2):
+                d = _dispatch(*shape, batch, storage)
+                seen.add(d["kernel"])
+                assert 0 <= d["lds_bytes"] <= 160 * 1024, (shape, batch, storage, d)
+                assert 64 <= d["threads"] <= 1024 and d["threads"] % 64 == 0, (shape, batch, storage, d)
+                assert d["workgroups"] >= 1
+                if d["ring_lines"]:
+                    assert d["ring_lines"] & (d["ring_lines"] - 1) == 0
+                    assert 0 < d["ring_lines_needed"] <= d["ring_lines"], (shape, batch, storage, d)
+                if d["kernel"] == 3:        # marching kernel: rows of at least 16 and at most 128 entries
+                    rows = k * k if storage == 0 else ((k + s - 1) // s) ** 2
+                    assert 16 <= rows <= 128 and d["strip"] in (32, 64) and d["segment"] % 2 == 0
+                    assert d["lines_per_step"] in (1, 2) and d["threads"] == 512
+                if d["kernel"] == 5:        # rectangle path: only the compiled (k, s)
+                    assert (s == 1 and k in (3, 5, 7)) or (s == 2 and k in (2, 3, 5, 7))
+                    assert d["lines_per_step"] == (4 if s == 1 else 2) and d["strip"] * d["lanes_per_row"] == 256
+                    assert d["segment"] % d["lines_per_step"] == 0
+                if d["kernel"] == 4:        # described rows: groups of lanes share the lines of a step
+                    groups = 256 // (d["strip"] * d["lanes_per_row"])
+                    assert groups >= 1 and 256 % (d["strip"] * d["lanes_per_row"]) == 0
+                    assert d["lines_per_step"] % groups == 0 and d["segment"] % d["lines_per_step"] == 0
+                if storage == 2:
+                    assert d["kernel"] in (4, 5)
+                else:
+                    assert d["kernel"] in (0, 1, 2, 3)
+                    if batch % 4:
+                        assert d["columns_per_lane"] == 1
+    assert seen == {0, 1, 2, 3, 4, 5}
+
+
+def test_dispatch_of_the_named_workloads():
+    want = {"small_32_k3": 0, "strided_256_k5_b64": 2, "headline_1024_k7_b1": 3, "headline_1024_k7_b16": 3,
+            "cnn_224_k3_b256": 2, "padheavy_512_k9_s3": 0, "padheavy_4096_k11_s4_b4": 3}
+    for name, kernel in want.items():
+        w = workloads.WORKLOADS[name]
+        assert _dispatch(*w.shape, w.batch)["kernel"] == kernel, name
+    d = _dispatch(*workloads.WORKLOADS["headline_1024_k7_b16"].shape, 16)
+    assert (d["strip"], d["segment"], d["ring_lines"], d["lines_per_step"], d["lds_bytes"], d["workgroups"]) == \
+        (64, 32, 16, 2, 73984, 512)
+    c = _dispatch(*workloads.WORKLOADS["headline_1024_k7_b16"].shape, 16, storage=2)
+    assert (c["kernel"], c["strip"], c["segment"], c["lines_per_step"], c["workgroups"]) == (5, 64, 32, 4, 512)
+    # several channels: the LDS tile kernel is not used (one launch per channel would not pay)
+    assert _dispatch(224, 224, 3, 1, 1, 16, 0, 64)["kernel"] == 1
+    assert _dispatch(1024, 1024, 7, 1, 3, 16, 0, 3)["kernel"] == 3
+    for bad in [(4, 4, 9, 1, 0, 1, 0, 1), (8, 8, 3, 1, 1, 0, 0, 1), (8, 8, 3, 1, 1, 1, 3, 1), (8, 8, 3, 1, 1, 1, 1, 2),
+                (300, 300, 256, 1, 0, 1, 2, 1)]:
+        with pytest.raises(cs.ConvError):
+            cs.conv_dispatch_info(*bad)
