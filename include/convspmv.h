@@ -138,6 +138,18 @@ int conv_compact_build(int m, int n, int k, int s, int p,
                        int32_t *row_desc_dev, float *ktab_dev,
                        void *stream, conv_plan **plan_out);
 
+/* The same storage for several input channels (see conv_csr_build_channels for
+ * the product): the descriptors depend on the shape only and are stored once,
+ * ktab_dev holds channels*k*k values, the table of channel ch at ktab_dev +
+ * ch*k*k, copied from kernels_dev.  conv_spmv takes the stacked planes and
+ * computes y = sum over ch of T_ch x_ch, one kernel per channel on `stream`,
+ * the later ones reading y and adding to it (plain loads and stores: the
+ * result is reproducible).  channels = 1 is conv_compact_build. */
+int conv_compact_build_channels(int m, int n, int k, int s, int p, int channels,
+                                const float *kernels_dev,
+                                int32_t *row_desc_dev, float *ktab_dev,
+                                void *stream, conv_plan **plan_out);
+
 /* Replace the kernel of a built T: rewrites the plan's vals array from a new
  * K of the same size (k*k fp32, row-major, device); row_ptr and col_idx do not
  * depend on K and are left alone.  The paper notes (Section 4.2) that the
@@ -192,8 +204,8 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch);
 /* What conv_spmv would launch for a shape, without a plan and without a GPU
  * (host only; 16-byte-aligned operands assumed): the kernel family and the
  * launch geometry the dispatch derives.  storage: 0 = CSR of T, 1 = CSC of T
- * (the plan applies T^T), 2 = structure-aware storage; channels > 1 only with
- * storage 0.  Status as for the build calls (CONV_EINVAL, CONV_EOVERFLOW,
+ * (the plan applies T^T), 2 = structure-aware storage; channels > 1 not with
+ * storage 1.  Status as for the build calls (CONV_EINVAL, CONV_EOVERFLOW,
  * CONV_ENULL).  For tests of the host logic and for reports. */
 typedef struct conv_dispatch {
     int kernel;             /* 0 row-group scalar, 1 row-group float4, 2 LDS tile, 3 LDS march,

@@ -24,6 +24,7 @@ EXPORTS = (
     "conv_csc_build", "conv_plan_is_transposed",
     "conv_compact_build", "conv_plan_is_compact",
     "conv_csr_build_channels", "conv_plan_channels", "conv_spmv_from_csc", "conv_dispatch_info",
+    "conv_compact_build_channels",
 )
 
 
@@ -70,6 +71,8 @@ def _load():
         lib.conv_plan_is_transposed.restype = i
         lib.conv_compact_build.argtypes = [i, i, i, i, i, vp, vp, vp, vp, ctypes.POINTER(vp)]
         lib.conv_compact_build.restype = i
+        lib.conv_compact_build_channels.argtypes = [i, i, i, i, i, i, vp, vp, vp, vp, ctypes.POINTER(vp)]
+        lib.conv_compact_build_channels.restype = i
         lib.conv_plan_is_compact.argtypes = [vp]
         lib.conv_plan_is_compact.restype = i
         lib.conv_csr_build_channels.argtypes = [i, i, i, i, i, i, vp, vp, vp, vp, vp, ctypes.POINTER(vp)]
@@ -182,7 +185,7 @@ class ConvPlan:
         """Bytes a CSR SpMM has to move: entries (index + value), row_ptr,
         x once, y once."""
         if self.compact:    # descriptors and the value table instead of the entries
-            return self.rows * 8 + self.k * self.k * 4 + self.cols * batch * 4 + self.rows * batch * 4
+            return (self.rows * 8 + self.k * self.k * 4) * self.channels + self.cols * batch * 4 + self.rows * batch * 4
         return (self.nnz * 4 * (1 + self.channels) + (self.rows + 1) * 4 + self.cols * batch * 4
                 + self.rows * batch * 4)
 
@@ -259,30 +262,32 @@ def conv_csr_build_channels(m, n, k, s, p, kernels, channels, stream=None) -> Co
     return plan
 
 
-def conv_compact_build(m, n, k, s, p, kernel, stream=None) -> ConvPlan:
+def conv_compact_build(m, n, k, s, p, kernel, stream=None, channels: int = 1) -> ConvPlan:
     """Build T in the structure-aware storage: plan.row_desc is int32 (rows, 2) = per row the
-    column of its first entry and the packed tap ranges, plan.ktab the k*k value table."""
+    column of its first entry and the packed tap ranges, plan.ktab the value table (k*k numbers
+    per channel; with channels > 1 the plan computes the sum over the stacked input planes)."""
     import torch
     lib = _load()
     mo, no = conv_out_shape(m, n, k, s, p)
     nnz = conv_nnz(m, n, k, s, p)
     if not (kernel.is_cuda and kernel.dtype == torch.float32 and kernel.is_contiguous()
-            and kernel.numel() == k * k):
-        raise ValueError("kernel must be a contiguous float32 device tensor with k*k elements")
+            and channels >= 1 and kernel.numel() == channels * k * k):
+        raise ValueError("kernel must be a contiguous float32 device tensor with channels*k*k elements")
     dev = kernel.device
-    if mo * no >= 2 ** 31 - 1 or m * n >= 2 ** 31 - 1:
+    if mo * no >= 2 ** 31 - 1 or m * n * channels >= 2 ** 31 - 1:
         raise ConvError(-3, "conv_compact_build%r" % ((m, n, k, s, p),))
     row_desc = torch.empty((mo * no, 2), dtype=torch.int32, device=dev)
-    ktab = torch.empty(k * k, dtype=torch.float32, device=dev)
+    ktab = torch.empty(channels * k * k, dtype=torch.float32, device=dev)
     handle = ctypes.c_void_p()
     with torch.cuda.device(dev):
         sh, _ = _stream_handle(stream)
-        st = lib.conv_compact_build(m, n, k, s, p, kernel.data_ptr(), row_desc.data_ptr(), ktab.data_ptr(), sh,
-                                    ctypes.byref(handle))
+        st = lib.conv_compact_build_channels(m, n, k, s, p, int(channels), kernel.data_ptr(), row_desc.data_ptr(),
+                                             ktab.data_ptr(), sh, ctypes.byref(handle))
     if st != 0:
         raise ConvError(st, "conv_compact_build%r" % ((m, n, k, s, p),))
     plan = ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, None, None, None, kernel)
     plan.compact = True
+    plan.channels = int(channels)
     plan.row_desc, plan.ktab = row_desc, ktab
     return plan
 

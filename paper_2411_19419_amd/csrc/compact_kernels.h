@@ -80,6 +80,7 @@ struct CompactGeom {
     int nl;               // ring lines (power of two); 0: no ring, every tap is read from global memory
     int ktab_lds;         // 1: the table is copied to LDS behind the ring
     int c_base;           // first batch column of this launch (wide batches take several launches)
+    int accum;            // 1: y += T x (second and later channels of a multi-channel sum)
 };
 
 constexpr int kCompactThreads = 256;
@@ -226,10 +227,11 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
         }
     };
     const unsigned y_lane_off = (unsigned)yy * g.batch * 4 + v * (unsigned)sizeof(elem_t);
-    auto store_y = [&](int xr_, const elem_t &a) {
+    auto y_row = [&](int xr_) {
         char *base = reinterpret_cast<char *>(y) + (((long long)xr_ * g.n_out + y0) * g.batch + c0) * 4;
-        __builtin_nontemporal_store(a, reinterpret_cast<elem_t *>(base + y_lane_off));
+        return reinterpret_cast<elem_t *>(base + y_lane_off);
     };
+    auto store_y = [&](int xr_, const elem_t &a) { __builtin_nontemporal_store(a, y_row(xr_)); };
 
     // ---- described path: one row, whatever its descriptor says
     auto row_described = [&](int xr_, int2 d, int lo_step, int hi_step) {
@@ -265,6 +267,7 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
                 }
             }
         }
+        if (g.accum) acc += *y_row(xr_);      // later channel of a multi-channel sum: y already holds the earlier ones
         store_y(xr_, acc);
     };
 
@@ -318,6 +321,14 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
                 elem_t acc[RV];
 #pragma unroll
                 for (int j = 0; j < RV; ++j) acc[j] = elem_t(0.0f);
+                // A later channel of a multi-channel sum adds to what the earlier launches left in
+                // y: requested here, used after the multiply-adds.
+                elem_t yprev[RV];
+#pragma unroll
+                for (int j = 0; j < RV; ++j) {
+                    yprev[j] = elem_t(0.0f);
+                    if (g.accum && xo + j < xb && yy < twc) yprev[j] = *y_row(xo + j);
+                }
                 auto read_line = [&](int di, elem_t (&dst)[KK]) {
                     const elem_t *src = lane_base + ((i0 + di) & (NL - 1)) * pitchE;
 #pragma unroll
@@ -347,7 +358,7 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
                 }
 #pragma unroll
                 for (int j = 0; j < RV; ++j)
-                    if (xo + j < xb && yy < twc) store_y(xo + j, acc[j]);
+                    if (xo + j < xb && yy < twc) store_y(xo + j, acc[j] + yprev[j]);
             } else {
 #pragma unroll
                 for (int j = 0; j < RV; ++j)

@@ -195,16 +195,23 @@ int conv_csc_build(int m, int n, int k, int s, int p, const float *kernel_dev, i
 
 int conv_compact_build(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *row_desc_dev,
                        float *ktab_dev, void *stream, conv_plan **plan_out) {
+    return conv_compact_build_channels(m, n, k, s, p, 1, kernel_dev, row_desc_dev, ktab_dev, stream, plan_out);
+}
+
+int conv_compact_build_channels(int m, int n, int k, int s, int p, int channels, const float *kernel_dev,
+                                int32_t *row_desc_dev, float *ktab_dev, void *stream, conv_plan **plan_out) {
     if (!plan_out) return CONV_ENULL;
     *plan_out = nullptr;
     int64_t mo, no;
     int st = check_shape(m, n, k, s, p, &mo, &no);
     if (st != CONV_OK) return st;
+    if (channels < 1) return CONV_EINVAL;
     if (k > 255) return CONV_EINVAL;                       // tap ranges are stored in 8 bits
     const int64_t nnz = conv_nnz(m, n, k, s, p);
     if (nnz < 0) return (int)nnz;
-    const int64_t rows = mo * no, cols = (int64_t)m * n;
-    if (rows >= kInt32Limit || cols >= kInt32Limit || mo * (int64_t)k > kInt32Limit || no * (int64_t)k > kInt32Limit)
+    const int64_t rows = mo * no, cols = (int64_t)m * n * channels;
+    if (rows >= kInt32Limit || cols >= kInt32Limit || mo * (int64_t)k > kInt32Limit || no * (int64_t)k > kInt32Limit ||
+        (int64_t)channels * k * k > kInt32Limit)
         return CONV_EOVERFLOW;
     const int64_t blocks = mo * ((no + kCompactBuildThreads - 1) / kCompactBuildThreads);
     if (blocks > kInt32Limit) return CONV_EOVERFLOW;
@@ -224,7 +231,7 @@ int conv_compact_build(int m, int n, int k, int s, int p, const float *kernel_de
     plan->axis_tab = nullptr;
     plan->device = 0;
     plan->transposed = false;
-    plan->channels = 1;
+    plan->channels = channels;
     plan->compact = true;
     plan->desc = reinterpret_cast<const int2 *>(row_desc_dev);
     plan->ktab = ktab_dev;
@@ -234,7 +241,7 @@ int conv_compact_build(int m, int n, int k, int s, int p, const float *kernel_de
     }
     hipStream_t q = (hipStream_t)stream;
     compact_rows_kernel<<<(unsigned)blocks, kCompactBuildThreads, 0, q>>>(plan->shape, reinterpret_cast<int2 *>(row_desc_dev));
-    compact_table_kernel<<<(k * k + 255) / 256, 256, 0, q>>>(kernel_dev, ktab_dev, k * k);
+    compact_table_kernel<<<(channels * k * k + 255) / 256, 256, 0, q>>>(kernel_dev, ktab_dev, channels * k * k);
     if (!hip_ok(hipGetLastError())) {
         delete plan;
         return CONV_EHIP;
@@ -246,7 +253,7 @@ int conv_compact_build(int m, int n, int k, int s, int p, const float *kernel_de
 int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream) {
     if (!plan || !kernel_dev) return CONV_ENULL;
     if (plan->compact) {
-        const int kk = plan->shape.k * plan->shape.k;
+        const int kk = plan->shape.k * plan->shape.k * plan->channels;
         compact_table_kernel<<<(kk + 255) / 256, 256, 0, (hipStream_t)stream>>>(kernel_dev, plan->ktab, kk);
         return hip_ok(hipGetLastError()) ? CONV_OK : CONV_EHIP;
     }
@@ -723,10 +730,15 @@ bool launch_compact_inst(const CompactChoice &c, const conv_plan *plan, const fl
     if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
     constexpr unsigned kMaxGridY = 65535;
     CompactGeom g = c.geom;
-    for (unsigned cb = 0; cb < c.col_blocks; cb += kMaxGridY) {      // column blocks beyond the grid limit: more launches
-        g.c_base = (int)(cb * (SCALAR ? 1u : 4u * LPR));
-        const dim3 grid((unsigned)(c.geom.blocks_per_xcd * kXcds), std::min(kMaxGridY, c.col_blocks - cb));
-        kern<<<grid, kCompactThreads, c.lds, q>>>(plan->desc, plan->ktab, x, y, g);
+    const size_t plane = (size_t)(plan->cols / plan->channels) * c.geom.batch, kk = (size_t)c.geom.k * c.geom.k;
+    // one launch per channel (its table, its operand plane): the first stores y, the others add to it
+    for (int ch = 0; ch < plan->channels; ++ch) {
+        g.accum = ch > 0;
+        for (unsigned cb = 0; cb < c.col_blocks; cb += kMaxGridY) {      // column blocks beyond the grid limit: more launches
+            g.c_base = (int)(cb * (SCALAR ? 1u : 4u * LPR));
+            const dim3 grid((unsigned)(c.geom.blocks_per_xcd * kXcds), std::min(kMaxGridY, c.col_blocks - cb));
+            kern<<<grid, kCompactThreads, c.lds, q>>>(plan->desc, plan->ktab + ch * kk, x + ch * plane, y, g);
+        }
     }
     return true;
 }
@@ -959,7 +971,7 @@ int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage
     int64_t mo, no;
     const int st = check_shape(m, n, k, s, p, &mo, &no);
     if (st != CONV_OK) return st;
-    if (batch < 1 || channels < 1 || storage < 0 || storage > 2 || (storage != 0 && channels != 1)) return CONV_EINVAL;
+    if (batch < 1 || channels < 1 || storage < 0 || storage > 2 || (storage == 1 && channels != 1)) return CONV_EINVAL;
     if (storage == 2 && k > 255) return CONV_EINVAL;
     const int64_t nnz = conv_nnz(m, n, k, s, p);
     if (nnz > kInt32Limit || mo * no >= kInt32Limit || (int64_t)m * n * channels >= kInt32Limit) return CONV_EOVERFLOW;

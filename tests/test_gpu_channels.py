@@ -109,3 +109,36 @@ def test_channel_errors():
     with pytest.raises(ValueError):                 # x must hold both planes
         cs.conv_spmv(plan, torch.zeros(64, device=dev), y, batch=1)
     plan.close()
+
+
+@pytest.mark.parametrize("shape,channels,batch", [
+    ((37, 53, 7, 1, 3), 3, 16), ((130, 67, 7, 1, 3), 2, 4), ((100, 90, 5, 2, 2), 4, 8), ((33, 200, 3, 1, 1), 8, 1),
+    ((75, 75, 9, 3, 8), 2, 3), ((6, 6, 2, 1, 5), 5, 7), ((224, 224, 7, 2, 3), 3, 16), ((56, 56, 3, 1, 1), 64, 4),
+    ((64, 64, 3, 1, 1), 1, 16), ((300, 301, 2, 2, 0), 2, 12),
+])
+def test_channel_sum_from_the_structure_aware_storage(shape, channels, batch):
+    m, n, k, s, p = shape
+    x, K = _case(shape, channels, batch, 6)
+    plan = cs.conv_compact_build(m, n, k, s, p, torch.from_numpy(K).to(device()), channels=channels)
+    assert binding._load().conv_plan_channels(plan._handle) == channels
+    assert np.array_equal(plan.row_desc.cpu().numpy(), oracle.compact_rows(m, n, k, s, p))
+    assert np.array_equal(plan.ktab.cpu().numpy().view(np.uint32), K.view(np.uint32))
+    y = torch.full((plan.rows * batch,), float("nan"), dtype=torch.float32, device=device())
+    cs.conv_spmv(plan, torch.from_numpy(x).to(device()), y, batch=batch)
+    y2 = cs.conv_spmv(plan, torch.from_numpy(x).to(device()), batch=batch)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)                        # the adds arrive in launch order: reproducible
+    got = y.cpu().numpy()
+    ref, scale = oracle.conv_channels(m, n, k, s, p, x, K, channels, batch=batch, want_scale=True)
+    live = scale > 0
+    assert not np.any(np.isnan(got)) and np.all(got[~live] == 0.0)
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    assert (np.max(err[live] / scale[live]) if np.any(live) else 0.0) <= REL_TOL
+    K2 = np.random.default_rng(7).standard_normal(channels * k * k).astype(np.float32)
+    cs.conv_update_kernel(plan, torch.from_numpy(K2).to(device()))
+    y3 = cs.conv_spmv(plan, torch.from_numpy(x).to(device()), batch=batch)
+    torch.cuda.synchronize()
+    ref2, scale2 = oracle.conv_channels(m, n, k, s, p, x, K2, channels, batch=batch, want_scale=True)
+    err2 = np.abs(y3.cpu().numpy().astype(np.float64) - ref2.astype(np.float64))
+    assert (np.max(err2[scale2 > 0] / scale2[scale2 > 0]) if np.any(scale2 > 0) else 0.0) <= REL_TOL
+    plan.close()

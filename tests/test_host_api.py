@@ -85,6 +85,7 @@ def test_argument_validation_without_a_gpu():
     assert lib.conv_csr_build_channels(4, 4, 3, 1, 1, 2, None, 16, 16, 16, None, ctypes.byref(h)) == -2
     assert lib.conv_csr_build_channels(30000, 30000, 1, 1, 0, 3, 16, 16, 16, 16, None, ctypes.byref(h)) == -3
     assert lib.conv_plan_channels(None) == -2
+    assert lib.conv_compact_build_channels(4, 4, 3, 1, 1, 0, 16, 16, 16, None, ctypes.byref(h)) == -1
     assert lib.conv_spmv_from_csc(None, 16, 32, 1, None) == -2
     assert lib.conv_out_shape(4, 4, 1, 1, 0, None, None) == -2
     h = ctypes.c_void_p()
