@@ -89,8 +89,10 @@ constexpr int kCompactThreads = 256;
 // path only, k, s, rv, nl from the geometry).  LPR lanes share a row, each with 4
 // batch columns (SCALAR: one lane, one column).  RV output lines per lane and step,
 // NL ring lines, XLD registers per thread that carry the next step's input lines
-// (0: the lines are copied after the step instead, behind a barrier).
-template <int KK, int SS, int LPR, bool SCALAR, int RV, int NL, int XLD>
+// (0: the lines are copied after the step instead, behind a barrier).  ACC: the rectangle
+// path adds to y (a later channel of a multi-channel sum); a compile-time switch there, so that
+// the single-channel kernel carries none of it; the described path looks at g.accum.
+template <int KK, int SS, int LPR, bool SCALAR, int RV, int NL, int XLD, bool ACC>
 __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const int2 *__restrict__ desc,
                                                                           const float *__restrict__ ktab,
                                                                           const float *__restrict__ x,
@@ -323,11 +325,13 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
                 for (int j = 0; j < RV; ++j) acc[j] = elem_t(0.0f);
                 // A later channel of a multi-channel sum adds to what the earlier launches left in
                 // y: requested here, used after the multiply-adds.
-                elem_t yprev[RV];
+                elem_t yprev[ACC ? RV : 1];
+                if constexpr (ACC) {
 #pragma unroll
-                for (int j = 0; j < RV; ++j) {
-                    yprev[j] = elem_t(0.0f);
-                    if (g.accum && xo + j < xb && yy < twc) yprev[j] = *y_row(xo + j);
+                    for (int j = 0; j < RV; ++j) {
+                        yprev[j] = elem_t(0.0f);
+                        if (xo + j < xb && yy < twc) yprev[j] = *y_row(xo + j);
+                    }
                 }
                 auto read_line = [&](int di, elem_t (&dst)[KK]) {
                     const elem_t *src = lane_base + ((i0 + di) & (NL - 1)) * pitchE;
@@ -358,7 +362,7 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
                 }
 #pragma unroll
                 for (int j = 0; j < RV; ++j)
-                    if (xo + j < xb && yy < twc) store_y(xo + j, acc[j] + yprev[j]);
+                    if (xo + j < xb && yy < twc) store_y(xo + j, ACC ? acc[j] + yprev[j] : acc[j]);
             } else {
 #pragma unroll
                 for (int j = 0; j < RV; ++j)

@@ -721,13 +721,20 @@ CompactChoice choose_compact(const conv_plan *plan, const float *x, const float 
     return c;
 }
 
-template <int KK, int SS, int LPR, bool SCALAR>
-bool launch_compact_inst(const CompactChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+template <int KK, int SS, int LPR, bool SCALAR, bool ACC>
+bool launch_compact_one(const CompactChoice &c, const CompactGeom &g, const conv_plan *plan, const float *ktab,
+                        const float *x, float *y, dim3 grid, hipStream_t q) {
     constexpr bool FAST = KK > 0;
     auto kern = spmm_compact_kernel<KK, SS, LPR, SCALAR, FAST ? rect_rv(SS) : 0, FAST ? kRectNl : 0,
-                                    FAST ? rect_xld(KK, SS, LPR) : 0>;
+                                    FAST ? rect_xld(KK, SS, LPR) : 0, ACC>;
     static thread_local bool allowed[64];
     if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
+    kern<<<grid, kCompactThreads, c.lds, q>>>(plan->desc, ktab, x, y, g);
+    return true;
+}
+
+template <int KK, int SS, int LPR, bool SCALAR>
+bool launch_compact_inst(const CompactChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
     constexpr unsigned kMaxGridY = 65535;
     CompactGeom g = c.geom;
     const size_t plane = (size_t)(plan->cols / plan->channels) * c.geom.batch, kk = (size_t)c.geom.k * c.geom.k;
@@ -737,7 +744,10 @@ bool launch_compact_inst(const CompactChoice &c, const conv_plan *plan, const fl
         for (unsigned cb = 0; cb < c.col_blocks; cb += kMaxGridY) {      // column blocks beyond the grid limit: more launches
             g.c_base = (int)(cb * (SCALAR ? 1u : 4u * LPR));
             const dim3 grid((unsigned)(c.geom.blocks_per_xcd * kXcds), std::min(kMaxGridY, c.col_blocks - cb));
-            kern<<<grid, kCompactThreads, c.lds, q>>>(plan->desc, plan->ktab + ch * kk, x + ch * plane, y, g);
+            const bool ok = (KK > 0 && ch > 0)
+                                ? launch_compact_one<KK, SS, LPR, SCALAR, (KK > 0)>(c, g, plan, plan->ktab + ch * kk, x + ch * plane, y, grid, q)
+                                : launch_compact_one<KK, SS, LPR, SCALAR, false>(c, g, plan, plan->ktab + ch * kk, x + ch * plane, y, grid, q);
+            if (!ok) return false;
         }
     }
     return true;
