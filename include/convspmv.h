@@ -126,7 +126,9 @@ int conv_csc_build(int m, int n, int k, int s, int p,
  *   ktab_dev     : k*k fp32, device, written: a copy of K, row-major.
  * Entry (da, db) of row r, da < r1, db < r2, is column base + da*n + db with
  * value ktab[(a_lo + da)*k + b_lo + db].  That is 8 bytes per row plus 4*k*k
- * instead of 8 bytes per entry.  Needs k <= 255 (CONV_EINVAL otherwise).
+ * instead of 8 bytes per entry.  Needs k <= 255 (CONV_EINVAL otherwise); the
+ * number of entries may exceed the int32 range (only rows and columns are
+ * indexed).
  * Both arrays are allocated by the caller and BORROWED by the plan.  conv_spmv
  * on the plan computes y = T x from these arrays as they are stored: the result
  * is the product with whatever matrix they describe, provided a_lo + r1 <= k,

@@ -984,7 +984,9 @@ int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage
     if (batch < 1 || channels < 1 || storage < 0 || storage > 2 || (storage == 1 && channels != 1)) return CONV_EINVAL;
     if (storage == 2 && k > 255) return CONV_EINVAL;
     const int64_t nnz = conv_nnz(m, n, k, s, p);
-    if (nnz > kInt32Limit || mo * no >= kInt32Limit || (int64_t)m * n * channels >= kInt32Limit) return CONV_EOVERFLOW;
+    // the structure-aware storage has no per-entry index, so its entry count is not limited to int32
+    if ((storage != 2 && nnz > kInt32Limit) || mo * no >= kInt32Limit || (int64_t)m * n * channels >= kInt32Limit)
+        return CONV_EOVERFLOW;
     // a plan without arrays: the dispatch looks at the shape, the storage and operand alignment only
     conv_plan plan{};
     plan.shape = ConvShape{m, n, k, s, p, (int)mo, (int)no};

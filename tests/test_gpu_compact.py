@@ -263,3 +263,21 @@ def test_compact_errors():
         cs.ConvMulti([plan], [x], [y], batch=1)
     assert lib.conv_plan_is_compact(plan._handle) == 1
     plan.close()
+
+
+def test_compact_beyond_the_csr_index_range():
+    """8192 x 8192, k = 7: 3.3e9 entries, more than int32 column-index arrays can address, so
+    conv_csr_build refuses the shape; the structure-aware storage indexes rows and columns only.
+    Descriptors in full and y in full against the oracle."""
+    shape, batch = (8192, 8192, 7, 1, 3), 1
+    m, n, k, s, p = shape
+    assert oracle.nnz_closed(*shape) > 2 ** 31
+    x, K = _rand(shape, batch, 23)
+    with pytest.raises(cs.ConvError) as e:
+        cs.conv_csr_build(m, n, k, s, p, torch.from_numpy(K).to(device()))
+    assert e.value.status == -3
+    plan = build_plan_c(shape, K)
+    assert plan.nnz == oracle.nnz_closed(*shape)
+    assert np.array_equal(plan.row_desc.cpu().numpy(), oracle.compact_rows(*shape))
+    check_apply(plan, shape, K, x, batch)
+    plan.close()
