@@ -44,12 +44,36 @@ def cpu_baseline(w, x, K, transposed=False):
     med = sorted(times)[len(times) // 2]
     nnz = oracle.nnz_closed(m, n, k, s, p)
     cores = int(os.environ.get("OMP_NUM_THREADS", "0")) or len(os.sched_getaffinity(0))
-    return {
+    out = {
         "value": nnz * w.batch / med / 1e9, "unit": "GMAC/s (useful: closed-form nnz x batch / s)",
         "seconds_per_apply": med, "cores": cores, "kind": "oracle",
         "sample": "whole workload %s (%d calls, median); explicit zero-pad + sliding window, "
                   "fp64 accumulation, OpenMP over output lines" % (w.name, len(times)),
+        "cpu_model": cpu_model(),
     }
+    # the same call on one thread (one call: the oracle is a correctness reference, not a tuned baseline)
+    try:
+        import ctypes
+        gomp = ctypes.CDLL("libgomp.so.1")
+        gomp.omp_set_num_threads(1)
+        t0 = time.perf_counter()
+        (oracle.conv_t if transposed else oracle.conv)(m, n, k, s, p, x, K, batch=w.batch)
+        out["one_thread_gmac_per_s"] = nnz * w.batch / (time.perf_counter() - t0) / 1e9
+        gomp.omp_set_num_threads(cores)
+    except OSError:
+        pass
+    return out
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def measured_traffic(variant):
@@ -344,6 +368,7 @@ def main():
         "build_ms": build_med,
         "build_over_apply": build_med / ms_per_step,
         "copy_gbs_same_bytes": copy_gbs,
+        "value_over_copy": gbs / copy_gbs,
         "copy_bytes_each_way": copy_bytes_each_way,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(plan.variant(w.batch)),
