@@ -641,7 +641,7 @@ constexpr int rect_xld(int k, int s, int lpr) {
 constexpr int kCompactTargetBlocks = 512;
 
 bool rect_compiled(int k, int s) {
-    return (s == 1 && (k == 3 || k == 5 || k == 7)) || (s == 2 && (k == 2 || k == 3 || k == 5 || k == 7));
+    return (s == 1 && (k == 1 || k == 3 || k == 5 || k == 7 || k == 9)) || (s == 2 && (k == 2 || k == 3 || k == 5 || k == 7));
 }
 
 CompactChoice choose_compact(const conv_plan *plan, const float *x, const float *y, int batch) {
@@ -764,9 +764,11 @@ bool launch_compact_k(const CompactChoice &c, const conv_plan *plan, const float
         }
     }
     switch (c.kk) {
+        case 1: return launch_compact_inst<1, 1, LPR, SCALAR>(c, plan, x, y, q);
         case 3: return launch_compact_inst<3, 1, LPR, SCALAR>(c, plan, x, y, q);
         case 5: return launch_compact_inst<5, 1, LPR, SCALAR>(c, plan, x, y, q);
         case 7: return launch_compact_inst<7, 1, LPR, SCALAR>(c, plan, x, y, q);
+        case 9: return launch_compact_inst<9, 1, LPR, SCALAR>(c, plan, x, y, q);
         default: return launch_compact_inst<0, 0, LPR, SCALAR>(c, plan, x, y, q);
     }
 }

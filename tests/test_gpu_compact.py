@@ -48,6 +48,8 @@ RECT = [   # (k, s) with a compiled rectangle path: several strips, segments, ra
     ((64, 64, 7, 1, 0), 16), ((50, 1000, 7, 1, 6), 16), ((1030, 260, 7, 1, 3), 1), ((90, 515, 5, 1, 2), 2),
     ((200, 257, 3, 1, 1), 1), ((70, 70, 7, 1, 3), 32), ((41, 600, 5, 1, 4), 4), ((9, 9, 7, 1, 3), 16),
     ((7, 300, 7, 1, 0), 8), ((300, 7, 7, 1, 0), 16), ((260, 130, 3, 1, 0), 12), ((33, 65, 7, 1, 5), 48),
+    ((200, 300, 9, 1, 4), 16), ((64, 500, 9, 1, 0), 4), ((150, 150, 1, 1, 0), 16), ((33, 77, 1, 1, 2), 8),
+    ((200, 1, 1, 1, 0), 6), ((90, 90, 9, 1, 8), 1), ((120, 40, 9, 1, 4), 2),
 ]
 RECT_S2 = [   # stride 2: two output lines per lane and step
     ((100, 90, 5, 2, 2), 16), ((224, 224, 7, 2, 3), 16), ((257, 513, 3, 2, 1), 1), ((300, 301, 2, 2, 0), 8),
@@ -56,10 +58,10 @@ RECT_S2 = [   # stride 2: two output lines per lane and step
 ]
 DESCRIBED = [
     ((100, 90, 5, 3, 2), 16), ((75, 75, 9, 3, 8), 4), ((90, 141, 11, 4, 5), 2), ((40, 40, 13, 1, 6), 3),
-    ((3, 50, 7, 5, 3), 5), ((6, 6, 2, 1, 5), 7), ((1, 1, 1, 5, 2), 3), ((200, 1, 1, 1, 0), 6),
+    ((3, 50, 7, 5, 3), 5), ((6, 6, 2, 1, 5), 7), ((1, 1, 1, 5, 2), 3), ((200, 1, 11, 1, 5), 6),
     ((300, 301, 2, 3, 0), 8), ((257, 513, 3, 4, 1), 1), ((64, 1000, 5, 3, 1), 4), ((224, 224, 7, 3, 3), 16),
     ((120, 120, 100, 5, 50), 4), ((260, 260, 255, 3, 0), 1), ((60, 70, 40, 1, 20), 16), ((500, 40, 4, 1, 2), 8),
-    ((31, 31, 6, 1, 9), 16), ((150, 150, 1, 1, 0), 16), ((97, 400, 2, 1, 1), 4),
+    ((31, 31, 6, 1, 9), 16), ((150, 150, 1, 3, 0), 16), ((97, 400, 2, 1, 1), 4),
 ]
 
 

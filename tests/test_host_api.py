@@ -206,7 +206,7 @@ def test_dispatch_geometry_is_consistent_over_many_shapes():
                     assert 16 <= rows <= 128 and d["strip"] in (32, 64) and d["segment"] % 2 == 0
                     assert d["lines_per_step"] in (1, 2) and d["threads"] == 512
                 if d["kernel"] == 5:        # rectangle path: only the compiled (k, s)
-                    assert (s == 1 and k in (3, 5, 7)) or (s == 2 and k in (2, 3, 5, 7))
+                    assert (s == 1 and k in (1, 3, 5, 7, 9)) or (s == 2 and k in (2, 3, 5, 7))
                     assert d["lines_per_step"] == (4 if s == 1 else 2) and d["strip"] * d["lanes_per_row"] == 256
                     assert d["segment"] % d["lines_per_step"] == 0
                 if d["kernel"] == 4:        # described rows: groups of lanes share the lines of a step
