@@ -248,7 +248,16 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
             const int lcol = (j_first - j_lo) * LPR + v;
             for (int da = 0; da < r1; ++da) {
                 const elem_t *lp = xs + __umul24((i_first + da) & nlm, pitchE) + lcol;
-                for (int db = 0; db < r2; ++db) fma_elem(acc, kp[db], lp[db * LPR]);
+                int db = 0;
+                for (; db + 4 <= r2; db += 4) {      // four independent LDS reads in flight per trip
+                    const elem_t e0 = lp[db * LPR], e1 = lp[(db + 1) * LPR], e2 = lp[(db + 2) * LPR], e3 = lp[(db + 3) * LPR];
+                    const float k0 = kp[db], k1 = kp[db + 1], k2 = kp[db + 2], k3 = kp[db + 3];
+                    fma_elem(acc, k0, e0);
+                    fma_elem(acc, k1, e1);
+                    fma_elem(acc, k2, e2);
+                    fma_elem(acc, k3, e3);
+                }
+                for (; db < r2; ++db) fma_elem(acc, kp[db], lp[db * LPR]);
                 kp += k;
             }
         } else {
