@@ -101,6 +101,26 @@ int64_t conv_nnz(int m, int n, int k, int s, int p) {
 
 namespace {
 
+// col_idx / vals fill of a built plan's matrix: through an LDS image of R rows' entries when the
+// rows are short enough for 32 of them (and the kernel) to fit, else the quad-walking kernel.
+template <bool COLS, bool TR>
+void launch_fill(const conv_plan *plan, const float *kernel_dev, int *idx_dev, float *vals_dev, hipStream_t q) {
+    const ConvShape &sh = plan->shape;
+    const int64_t l1 = TR ? sh.m : sh.m_out, l2 = TR ? sh.n : sh.n_out;
+    int R = 256;
+    while (R > 32 && (int64_t)R * plan->max_row_nnz > kFillStageEntries) R >>= 1;
+    const int64_t cap = ((int64_t)R * plan->max_row_nnz + 4 + 3) & ~3LL;
+    const int64_t lds = ((((int64_t)R + 1 + (int64_t)sh.k * sh.k + 3) & ~3LL) + 2 * cap) * 4;
+    const int64_t blocks = l1 * ((l2 + R - 1) / R);
+    if ((int64_t)R * plan->max_row_nnz <= kFillStageEntries && lds <= 64 * 1024 && blocks <= kInt32Limit) {
+        csr_fill_staged_kernel<COLS, TR><<<(unsigned)blocks, kFillThreads, (size_t)lds, q>>>(
+            sh, plan->axis_tab, kernel_dev, idx_dev, vals_dev, R, (int)cap);
+    } else {
+        const unsigned quad_blocks = (unsigned)(l1 * ((l2 + kFillRows - 1) / kFillRows));
+        csr_fill_kernel<COLS, TR><<<quad_blocks, kFillThreads, 0, q>>>(sh, plan->axis_tab, kernel_dev, idx_dev, vals_dev);
+    }
+}
+
 template <bool TR>
 int build_impl(int m, int n, int k, int s, int p, int channels, const float *kernel_dev, int32_t *ptr_dev,
                int32_t *idx_dev, float *vals_dev, void *stream, conv_plan **plan_out) {
@@ -157,11 +177,9 @@ int build_impl(int m, int n, int k, int s, int p, int channels, const float *ker
     axis_prefix_kernel<TR><<<2, kAxisThreads, 0, q>>>(plan->shape, plan->axis_tab);
     row_ptr_kernel<TR><<<(unsigned)rp_blocks, kRowPtrThreads, 0, q>>>(plan->shape, plan->axis_tab, ptr_dev);
     if (nnz > 0) {
-        csr_fill_kernel<true, TR><<<(unsigned)fill_blocks, kFillThreads, 0, q>>>(plan->shape, plan->axis_tab,
-                                                                               kernel_dev, idx_dev, vals_dev);
+        launch_fill<true, TR>(plan, kernel_dev, idx_dev, vals_dev, q);
         for (int ch = 1; ch < channels; ++ch)      // the other channels share the indices: values only
-            csr_fill_kernel<false, TR><<<(unsigned)fill_blocks, kFillThreads, 0, q>>>(
-                plan->shape, plan->axis_tab, kernel_dev + (size_t)ch * k * k, nullptr, vals_dev + (size_t)ch * nnz);
+            launch_fill<false, TR>(plan, kernel_dev + (size_t)ch * k * k, nullptr, vals_dev + (size_t)ch * nnz, q);
     }
     if (!hip_ok(hipGetLastError())) {
         (void)hipFree(plan->axis_tab);
@@ -258,17 +276,14 @@ int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream) {
         return hip_ok(hipGetLastError()) ? CONV_OK : CONV_EHIP;
     }
     if (plan->nnz == 0) return CONV_OK;
-    const int64_t l1 = plan->transposed ? plan->shape.m : plan->shape.m_out;
-    const int64_t l2 = plan->transposed ? plan->shape.n : plan->shape.n_out;
-    const unsigned fill_blocks = (unsigned)(l1 * ((l2 + kFillRows - 1) / kFillRows));
     const size_t kk = (size_t)plan->shape.k * plan->shape.k;
     for (int ch = 0; ch < plan->channels; ++ch) {
         if (plan->transposed)
-            csr_fill_kernel<false, true><<<fill_blocks, kFillThreads, 0, (hipStream_t)stream>>>(
-                plan->shape, plan->axis_tab, kernel_dev + ch * kk, nullptr, plan->vals + (size_t)ch * plan->nnz);
+            launch_fill<false, true>(plan, kernel_dev + ch * kk, nullptr, plan->vals + (size_t)ch * plan->nnz,
+                                     (hipStream_t)stream);
         else
-            csr_fill_kernel<false, false><<<fill_blocks, kFillThreads, 0, (hipStream_t)stream>>>(
-                plan->shape, plan->axis_tab, kernel_dev + ch * kk, nullptr, plan->vals + (size_t)ch * plan->nnz);
+            launch_fill<false, false>(plan, kernel_dev + ch * kk, nullptr, plan->vals + (size_t)ch * plan->nnz,
+                                      (hipStream_t)stream);
     }
     if (!hip_ok(hipGetLastError())) return CONV_EHIP;
     return CONV_OK;
