@@ -256,13 +256,16 @@ __global__ __launch_bounds__(kFillThreads) void csr_fill_kernel(ConvShape sh, co
 // The image is shifted by `lead` = span start mod 4 entries, which makes LDS quads and array
 // quads coincide.  R (a power of two, 32..256) is chosen by the host so that the
 // image fits: LDS holds rel[R+1], the k*k kernel numbers, and `cap` entries of each array.
+// With row_ptr given the kernel writes the row pointers of its rows as well (the build then
+// needs no separate row_ptr launch).
 constexpr int kFillStageEntries = 6400;     // entries of one span the LDS image may hold
 
 template <bool COLS, bool TR>
 __global__ __launch_bounds__(kFillThreads) void csr_fill_staged_kernel(ConvShape sh, const int *__restrict__ tab,
                                                                        const float *__restrict__ kernel,
                                                                        int *__restrict__ col_idx,
-                                                                       float *__restrict__ vals, int R, int cap) {
+                                                                       float *__restrict__ vals, int R, int cap,
+                                                                       int *__restrict__ row_ptr) {
     typedef int ivec4 __attribute__((ext_vector_type(4)));
     typedef float fvec4 __attribute__((ext_vector_type(4)));
     extern __shared__ int fill_smem[];
@@ -285,6 +288,11 @@ __global__ __launch_bounds__(kFillThreads) void csr_fill_staged_kernel(ConvShape
     __syncthreads();
     const long long base = (long long)p1 * P2[L2] + (long long)r1 * p2a;
     const int total = r1 * rel[nrows];               // at most R * (longest row) <= kFillStageEntries
+    if (row_ptr) {
+        // the row pointers of these rows come for free: row_ptr[x * L2 + y] = P1[x] * S2 + r1 * P2[y]
+        for (int i = tid; i < nrows; i += kFillThreads) row_ptr[(long long)x * L2 + ya + i] = (int)(base + r1 * rel[i]);
+        if (blockIdx.x == gridDim.x - 1 && tid == 0) row_ptr[(long long)L1 * L2] = (int)(base + total);
+    }
     if (total == 0) return;                          // uniform: these rows have no entries
     const int lead = (int)(base & 3);
     // first stored kernel row and its input line (T), or the first covering window line (T^T)

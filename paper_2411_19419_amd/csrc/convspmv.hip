@@ -103,8 +103,10 @@ namespace {
 
 // col_idx / vals fill of a built plan's matrix: through an LDS image of R rows' entries when the
 // rows are short enough for 32 of them (and the kernel) to fit, else the quad-walking kernel.
+// Returns true when the launch also wrote row_ptr (staged kernel with row_ptr_dev given).
 template <bool COLS, bool TR>
-void launch_fill(const conv_plan *plan, const float *kernel_dev, int *idx_dev, float *vals_dev, hipStream_t q) {
+bool launch_fill(const conv_plan *plan, const float *kernel_dev, int *idx_dev, float *vals_dev, hipStream_t q,
+                 int *row_ptr_dev = nullptr) {
     const ConvShape &sh = plan->shape;
     const int64_t l1 = TR ? sh.m : sh.m_out, l2 = TR ? sh.n : sh.n_out;
     int R = 256;
@@ -114,11 +116,12 @@ void launch_fill(const conv_plan *plan, const float *kernel_dev, int *idx_dev, f
     const int64_t blocks = l1 * ((l2 + R - 1) / R);
     if ((int64_t)R * plan->max_row_nnz <= kFillStageEntries && lds <= 64 * 1024 && blocks <= kInt32Limit) {
         csr_fill_staged_kernel<COLS, TR><<<(unsigned)blocks, kFillThreads, (size_t)lds, q>>>(
-            sh, plan->axis_tab, kernel_dev, idx_dev, vals_dev, R, (int)cap);
-    } else {
-        const unsigned quad_blocks = (unsigned)(l1 * ((l2 + kFillRows - 1) / kFillRows));
-        csr_fill_kernel<COLS, TR><<<quad_blocks, kFillThreads, 0, q>>>(sh, plan->axis_tab, kernel_dev, idx_dev, vals_dev);
+            sh, plan->axis_tab, kernel_dev, idx_dev, vals_dev, R, (int)cap, row_ptr_dev);
+        return row_ptr_dev != nullptr;
     }
+    const unsigned quad_blocks = (unsigned)(l1 * ((l2 + kFillRows - 1) / kFillRows));
+    csr_fill_kernel<COLS, TR><<<quad_blocks, kFillThreads, 0, q>>>(sh, plan->axis_tab, kernel_dev, idx_dev, vals_dev);
+    return false;
 }
 
 template <bool TR>
@@ -175,9 +178,12 @@ int build_impl(int m, int n, int k, int s, int p, int channels, const float *ker
     }
     hipStream_t q = (hipStream_t)stream;
     axis_prefix_kernel<TR><<<2, kAxisThreads, 0, q>>>(plan->shape, plan->axis_tab);
-    row_ptr_kernel<TR><<<(unsigned)rp_blocks, kRowPtrThreads, 0, q>>>(plan->shape, plan->axis_tab, ptr_dev);
+    // the staged fill writes row_ptr on its way; otherwise (no entries, or rows too long for it) its own kernel does
+    bool have_row_ptr = false;
+    if (nnz > 0) have_row_ptr = launch_fill<true, TR>(plan, kernel_dev, idx_dev, vals_dev, q, ptr_dev);
+    if (!have_row_ptr)
+        row_ptr_kernel<TR><<<(unsigned)rp_blocks, kRowPtrThreads, 0, q>>>(plan->shape, plan->axis_tab, ptr_dev);
     if (nnz > 0) {
-        launch_fill<true, TR>(plan, kernel_dev, idx_dev, vals_dev, q);
         for (int ch = 1; ch < channels; ++ch)      // the other channels share the indices: values only
             launch_fill<false, TR>(plan, kernel_dev + (size_t)ch * k * k, nullptr, vals_dev + (size_t)ch * nnz, q);
     }
