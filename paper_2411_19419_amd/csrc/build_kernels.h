@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kFillThreads) void csr_fill_kernel(ConvShape sh, co
 // full lines (plain stores: with nothing but writes in flight they measured 18 % faster than
 // non-temporal ones, the opposite of what the apply kernels see next to their read streams).
 // The image is shifted by `lead` = span start mod 4 entries, which makes LDS quads and array
-// quads coincide.  R (a power of two, 32..256) is chosen by the host so that the
+// quads coincide.  R (a power of two, 1..256) is chosen by the host so that the
 // image fits: LDS holds rel[R+1], the k*k kernel numbers, and `cap` entries of each array.
 // With row_ptr given the kernel writes the row pointers of its rows as well (the build then
 // needs no separate row_ptr launch).

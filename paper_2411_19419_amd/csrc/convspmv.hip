@@ -101,8 +101,8 @@ int64_t conv_nnz(int m, int n, int k, int s, int p) {
 
 namespace {
 
-// col_idx / vals fill of a built plan's matrix: through an LDS image of R rows' entries when the
-// rows are short enough for 32 of them (and the kernel) to fit, else the quad-walking kernel.
+// col_idx / vals fill of a built plan's matrix: through an LDS image of R rows' entries (R = 256
+// down to 1) when at least one row and the kernel fit, else the quad-walking kernel.
 // Returns true when the launch also wrote row_ptr (staged kernel with row_ptr_dev given).
 template <bool COLS, bool TR>
 bool launch_fill(const conv_plan *plan, const float *kernel_dev, int *idx_dev, float *vals_dev, hipStream_t q,
@@ -110,7 +110,7 @@ bool launch_fill(const conv_plan *plan, const float *kernel_dev, int *idx_dev, f
     const ConvShape &sh = plan->shape;
     const int64_t l1 = TR ? sh.m : sh.m_out, l2 = TR ? sh.n : sh.n_out;
     int R = 256;
-    while (R > 32 && (int64_t)R * plan->max_row_nnz > kFillStageEntries) R >>= 1;
+    while (R > 1 && (int64_t)R * plan->max_row_nnz > kFillStageEntries) R >>= 1;
     const int64_t cap = ((int64_t)R * plan->max_row_nnz + 4 + 3) & ~3LL;
     const int64_t lds = ((((int64_t)R + 1 + (int64_t)sh.k * sh.k + 3) & ~3LL) + 2 * cap) * 4;
     const int64_t blocks = l1 * ((l2 + R - 1) / R);

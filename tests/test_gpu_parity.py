@@ -80,6 +80,12 @@ def test_named_workloads_full_size(name):
     ((1, 1, 1, 5, 2), 3),         # no entries at all
     ((1, 1, 1, 1, 0), 1),
     ((200, 1, 1, 1, 0), 6),
+    # long rows: the build stages 16, 4, 2, 1 rows per workgroup, then walks quads (rows beyond its LDS image)
+    ((60, 70, 20, 1, 10), 3),
+    ((50, 50, 30, 2, 15), 2),
+    ((64, 64, 45, 1, 22), 1),
+    ((70, 70, 60, 1, 30), 1),
+    ((90, 90, 80, 1, 40), 1),
 ])
 def test_ragged_and_degenerate_shapes(shape, batch):
     x, K = _rand(shape, batch, 7)

@@ -45,6 +45,8 @@ def test_transposed_exhaustive_tiny_grid():
     ((75, 75, 9, 3, 8), 4), ((90, 141, 11, 4, 5), 2), ((40, 40, 13, 1, 6), 3), ((3, 50, 7, 2, 3), 5),
     ((6, 6, 2, 1, 5), 7), ((1, 1, 1, 5, 2), 3), ((200, 1, 1, 1, 0), 6), ((300, 301, 2, 2, 0), 8),
     ((257, 513, 3, 2, 1), 1), ((64, 1000, 5, 3, 1), 4),
+    ((60, 70, 20, 1, 10), 3), ((50, 50, 30, 2, 15), 2), ((64, 64, 45, 1, 22), 1), ((70, 70, 60, 1, 30), 1),
+    ((90, 90, 80, 1, 40), 1),          # long rows: every staging width of the build, and its fallback
 ])
 def test_transposed_ragged_and_degenerate_shapes(shape, batch):
     u, K = _rand_t(shape, batch, 7)
