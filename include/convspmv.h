@@ -182,10 +182,15 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
  * come from conv_csc_build (CONV_EINVAL otherwise); x_dev has m*n*batch
  * elements, y_dev m_out*n_out*batch, both batch-minor.  By columns the product
  * is a scatter: y is zeroed, then every stored entry adds vals[e]*x[column] to
- * y[row_idx[e]] with one hardware float add.  The result is that of conv_spmv
- * on the CSR plan of the same T up to the order of the additions, which here
- * depends on timing: repeated calls agree to rounding, not bit for bit.  The
- * arrays are read as stored (every row_idx must be in [0, m_out*n_out)). */
+ * y[row_idx[e]].  The sums of a tile of neighbouring pixels are collected on
+ * chip and added to y with hardware float adds (for 3 <= ceil(k/s) <= 32;
+ * otherwise every entry is added to y directly).  The result is that of
+ * conv_spmv on the CSR plan of the same T up to the order of the additions,
+ * which here depends on timing: repeated calls agree to rounding, not bit for
+ * bit.  The arrays are read as stored: every row_idx must be in
+ * [0, m_out*n_out), col_ptr non-decreasing, and the row indices of one column
+ * pairwise different, as conv_csc_build writes them (a row stored twice in
+ * one column may lose one of its two contributions). */
 int conv_spmv_from_csc(const conv_plan *plan, const float *x_dev, float *y_dev, int batch, void *stream);
 
 /* Shape and size queries on a plan (host only).  conv_plan_is_transposed

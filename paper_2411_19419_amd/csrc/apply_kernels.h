@@ -147,6 +147,205 @@ __global__ __launch_bounds__(kGatherThreads) void spmm_scatter_kernel(
     }
 }
 
+// The same scatter with the sums kept on chip.  A workgroup takes a tile of ti x tj input
+// pixels (columns of T) and a chunk of batch columns, and keeps in LDS a window of outputs
+// around the ones those columns reach (Section 2: pixel i is covered by the windows x with
+// 0 <= i + p - s x < k, so ti lines reach at most (ti + k - 2)/s + 1 output lines).  The
+// window is wx runs of wy consecutive rows, run lx starting at row base + lx * n_out; an
+// entry whose row is not in it (none is, for arrays this library built) is added to y directly.
+//
+// LDS float atomics run one lane at a time on this chip (about 190 clocks per wave
+// instruction against 8 for a read, an add and a write), so the sums are plain
+// read-add-write and the lanes are laid out so that no two of them ever meet in one slot:
+//  * each wave owns VB batch columns and a window image of its own, so waves never share;
+//  * the 64 lanes of one step are consecutive entries of ONE column (each lane adds its
+//    entry's VB products), and the entries of a column have pairwise different rows (the
+//    arrays come from conv_csc_build, which writes every (row, column) pair once);
+//  * a wave's LDS instructions execute in order, so the writes of one step are seen by the
+//    reads of the next.
+// The entries of one tile line are contiguous in the arrays; the workgroup copies them into
+// an LDS stage one line ahead of their use, so that the waves (which all walk the same
+// entries, for different batch columns) never wait for memory inside the walk.  At the end
+// the workgroup adds its windows to y, which fill_zero_kernel cleared: about
+// (1 + (k-1)/(s ti)) (1 + (k-1)/(s tj)) adds per output instead of one per entry.
+constexpr int kCscStage = 1024;      // most entries of one tile line (tj columns)
+
+struct CscTileGeom {
+    int m, n, n_out, k, s, p, batch;
+    int ti, tj, tiles_j;           // tile: ti lines of tj pixels, tj < 64; tiles per line of tiles
+    int wx, wy;                    // window: runs x rows per run
+    int limit;                     // (wx - 1) * n_out + wy, at most 2^21: rows base .. base + limit - 1 can be in the window
+    int stage;                     // entries per stage buffer, tj * (most entries of a column) <= kCscStage
+    int ptrs;                      // ints set aside for the column pointers, ti * (tj + 1) rounded up to 4
+    float inv_wy, inv_n_out;
+};
+
+__device__ __forceinline__ int first_window(int t0, int k, int s, int p) {   // smallest x >= 0 with t0 + p - s x < k
+    const long long num = (long long)t0 + p - k + 1;
+    return num <= 0 ? 0 : (int)((num + s - 1) / s);
+}
+
+__device__ __forceinline__ void wave_lds_order() {    // later LDS accesses of this wave stay behind earlier ones
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <int VB, int W>
+__global__ __launch_bounds__(W *kWave) void spmm_csc_tile_kernel(
+    const int *__restrict__ col_ptr, const int *__restrict__ row_idx, const float *__restrict__ vals,
+    const float *__restrict__ x, float *__restrict__ y, const CscTileGeom g) {
+    constexpr int NT = W * kWave, BC = W * VB;   // threads; batch columns per pass
+    constexpr int PER = kCscStage / NT;          // staged entries per thread
+    extern __shared__ __align__(16) int lds[];
+    int2 *const stage = reinterpret_cast<int2 *>(lds);                     // [2][g.stage] (window slot or -1, value bits)
+    int *const ptrs = lds + 4 * g.stage;                                   // [ti][tj + 1] column pointers
+    float *const win = reinterpret_cast<float *>(ptrs + g.ptrs);           // [W][VB / 4][wx][wy][4] ([W][wx][wy][VB] for VB < 4)
+    const int tile_i = (int)blockIdx.x / g.tiles_j, tile_j = (int)blockIdx.x - tile_i * g.tiles_j;
+    const int i0 = tile_i * g.ti, j0 = tile_j * g.tj;
+    // first row of the window; below 2^31 like every row
+    const int base = first_window(i0, g.k, g.s, g.p) * g.n_out + first_window(j0, g.k, g.s, g.p);
+    const int tid = (int)threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave), lane = tid % kWave;
+    const int slots = g.wx * g.wy, image = slots * VB;
+    float *const mine = win + wave * image;
+    const int lines = min(g.ti, g.m - i0), ncols = min(g.tj, g.n - j0);
+    const long long tile_col0 = (long long)i0 * g.n + j0;
+    const int skip = g.n_out - g.wy;             // rows between the end of one run and the start of the next
+
+    for (int t = tid; t < lines * (g.tj + 1); t += NT) {
+        const int li = t / (g.tj + 1), cj = t - li * (g.tj + 1);
+        ptrs[t] = col_ptr[tile_col0 + (long long)li * g.n + min(cj, ncols)];
+    }
+    for (int c0 = blockIdx.y * BC; c0 < g.batch; c0 += gridDim.y * BC) {      // uniform over the block
+        for (int t = tid; t < image * W; t += NT) win[t] = 0.0f;
+        __syncthreads();
+        // Entry `at` of tile line li (row, value) into a stage buffer: its window slot, found here once
+        // for all waves and off their chain of sums.  An entry outside the window is added to y on the
+        // spot, for every batch column of this pass, and staged as slot -1.
+        auto put = [&](int2 *buf, int li, int at, int row, int value) {
+            const int rp = row - base;
+            const bool near = (unsigned)rp < (unsigned)g.limit;
+            const int lx = div_small(near ? rp : 0, g.inv_n_out), ly = rp - lx * g.n_out;
+            int slot = rp - lx * skip;
+            if (!near || ly >= g.wy) {
+                slot = -1;
+                const int *lp = ptrs + li * (g.tj + 1);
+                const int e = lp[0] + at;
+                int t = 0;
+                while (t + 1 < ncols && e >= lp[t + 1]) ++t;
+                const float *xc = x + (tile_col0 + (long long)li * g.n + t) * g.batch;
+                for (int b = c0; b < min(c0 + BC, g.batch); ++b)
+                    unsafeAtomicAdd(y + (long long)row * g.batch + b, __int_as_float(value) * xc[b]);
+            }
+            buf[at] = make_int2(slot, value);
+        };
+        const int cw = c0 + wave * VB;           // this wave's first batch column
+        // lane l holds the wave's VB inputs of column l of a line
+        auto load_x = [&](float (&xl)[VB], long long col0) {
+            const float *xp = x + (col0 + min(lane, ncols - 1)) * g.batch + cw;
+            if (cw + VB <= g.batch) {
+#pragma unroll
+                for (int v = 0; v < VB; ++v) xl[v] = xp[v];
+            } else {
+#pragma unroll
+                for (int v = 0; v < VB; ++v) xl[v] = cw + v < g.batch ? xp[v] : 0.0f;
+            }
+        };
+        float xl_next[VB];
+        load_x(xl_next, tile_col0);
+        {   // line 0 into the stage
+            const int beg = ptrs[0], count = min(ptrs[ncols] - beg, g.stage);
+            for (int t = tid; t < count; t += NT) put(stage, 0, t, row_idx[beg + t], __float_as_int(vals[beg + t]));
+        }
+        __syncthreads();
+        for (int li = 0; li < lines; ++li) {
+            const int2 *const cur = stage + (li & 1) * g.stage;
+            const int cp = ptrs[li * (g.tj + 1) + min(lane, ncols)];       // lane l: pointer of column l
+            // the next line's entries and inputs are asked for now and staged after this line's sums
+            int rows_next[PER], vals_next[PER];
+            int count_next = 0;
+            float xl[VB];
+#pragma unroll
+            for (int v = 0; v < VB; ++v) xl[v] = xl_next[v];
+            if (li + 1 < lines) {
+                load_x(xl_next, tile_col0 + (long long)(li + 1) * g.n);
+                const int beg_next = ptrs[(li + 1) * (g.tj + 1)];
+                count_next = min(ptrs[(li + 1) * (g.tj + 1) + ncols] - beg_next, g.stage);
+#pragma unroll
+                for (int u = 0; u < PER; ++u) {
+                    rows_next[u] = vals_next[u] = 0;
+                    if (u * NT + tid < count_next) {
+                        rows_next[u] = row_idx[beg_next + u * NT + tid];
+                        vals_next[u] = __float_as_int(vals[beg_next + u * NT + tid]);
+                    }
+                }
+            }
+            const int line_beg = __builtin_amdgcn_readfirstlane(cp);
+            // entries e .. of a column that ends at `end`, one per lane, from the stage
+            auto fetch = [&](int e, int end) { return cur[max(min(min(e, end - 1) - line_beg, g.stage - 1), 0)]; };
+            int end = line_beg;
+            int2 ahead = fetch(line_beg + lane, __builtin_amdgcn_readlane(cp, 1));
+            for (int t = 0; t < ncols; ++t) {
+                const int beg = end;
+                end = __builtin_amdgcn_readlane(cp, t + 1);
+                int2 ev = ahead;
+                // the first 64 entries of the next column are fetched before this column's sums
+                if (t + 1 < ncols) ahead = fetch(end + lane, __builtin_amdgcn_readlane(cp, t + 2));
+                if (beg >= end) continue;
+                float xq[VB];
+#pragma unroll
+                for (int v = 0; v < VB; ++v)
+                    xq[v] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(xl[v]), t));
+                for (int e0 = beg; e0 < end; e0 += kWave) {      // entries e0 .. e0 + 63 of column t
+                    if (e0 > beg) ev = fetch(e0 + lane, end);
+                    const float val = __int_as_float(ev.y);
+                    if (e0 + lane < end && ev.x >= 0) {
+                        if (VB % 4 == 0) {
+                            // planes of four batch columns: neighbouring slots are 16 bytes apart in each
+                            float4 *const slot = reinterpret_cast<float4 *>(mine) + ev.x;
+                            float4 q[VB / 4 + 1];
+#pragma unroll
+                            for (int v = 0; v < VB / 4; ++v) q[v] = slot[v * slots];
+#pragma unroll
+                            for (int v = 0; v < VB / 4; ++v) {
+                                q[v].x = fmaf(val, xq[4 * v], q[v].x);
+                                q[v].y = fmaf(val, xq[4 * v + 1], q[v].y);
+                                q[v].z = fmaf(val, xq[4 * v + 2], q[v].z);
+                                q[v].w = fmaf(val, xq[4 * v + 3], q[v].w);
+                            }
+#pragma unroll
+                            for (int v = 0; v < VB / 4; ++v) slot[v * slots] = q[v];
+                        } else {
+                            float *const slot = mine + ev.x * VB;
+#pragma unroll
+                            for (int v = 0; v < VB; ++v) slot[v] = fmaf(val, xq[v], slot[v]);
+                        }
+                    }
+                    wave_lds_order();
+                }
+            }
+            if (li + 1 < lines) {
+                int2 *const nxt = stage + ((li + 1) & 1) * g.stage;
+#pragma unroll
+                for (int u = 0; u < PER; ++u)
+                    if (u * NT + tid < count_next) put(nxt, li + 1, u * NT + tid, rows_next[u], vals_next[u]);
+            }
+            __syncthreads();
+        }
+        // consecutive threads take the batch columns of one output, so that their adds fill a line of y
+        for (int t = tid; t < g.wx * g.wy * BC; t += NT) {
+            const int b = t % BC, slot = t / BC;
+            const int bw = b % VB;
+            const float v = VB % 4 == 0 ? win[(b / VB) * image + ((bw / 4) * slots + slot) * 4 + bw % 4]
+                                        : win[(b / VB) * image + slot * VB + bw];
+            const int lx = div_small(slot, g.inv_wy);
+            if (v != 0.0f && c0 + b < g.batch)      // a slot that received a sum stands for a row of T
+                unsafeAtomicAdd(y + ((long long)base + slot + (long long)lx * skip) * g.batch + c0 + b, v);
+        }
+        __syncthreads();
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Many small products in one launch.  The paper's experiment (Section 4.1)
 // applies 123 small, independent transformations (the DenseNet121 layer shapes

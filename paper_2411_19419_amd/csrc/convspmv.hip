@@ -850,6 +850,90 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
     return CONV_OK;
 }
 
+}  // extern "C"
+
+// Launch shape of the on-chip scatter: VB batch columns per wave, W waves per workgroup (W * VB
+// batch columns per pass), tj < 64 pixels per tile line (the lanes of a wave hold one line's
+// column pointers) with a line's entries within the stage.  The kernel is bound by the number
+// of instructions it issues and needs many resident waves, so small LDS footprints are tried
+// first: among the tiles within a footprint the one with the smallest window per pixel wins; a
+// launch too small to fill the chip is charged for the idle units.  Not ok when no tile fits
+// (k above about 32 s) or when the columns are so short (k < 3 s) that a step, which takes the
+// entries of one column, would leave most lanes idle: then every entry is added to y directly.
+constexpr size_t kCscTileLds[3] = {20 * 1024, 40 * 1024, 64 * 1024};
+constexpr double kCscTileWindowGoal = 6.0;     // window slots per pixel that end the search for a larger footprint
+constexpr int kCscTileShortColumn = 9;         // columns of fewer entries leave most lanes of a step idle
+
+struct CscTileChoice {
+    bool ok;
+    CscTileGeom g;
+    int vb, waves;
+    size_t lds;
+    dim3 grid;
+};
+
+static CscTileChoice choose_csc_tile(const conv_plan *plan, int batch) {
+    const ConvShape &sh = plan->shape;
+    CscTileChoice c{};
+    if (batch >= 9) { c.vb = 4; c.waves = 4; }
+    else if (batch >= 5) { c.vb = 4; c.waves = 2; }
+    else if (batch >= 3) { c.vb = 4; c.waves = 1; }
+    else { c.vb = batch; c.waves = 1; }
+    const int bc = c.waves * c.vb;
+    const int chunks = std::min((batch + bc - 1) / bc, 65535);
+    CscTileGeom g{};
+    g.m = sh.m; g.n = sh.n; g.n_out = sh.n_out; g.k = sh.k; g.s = sh.s; g.p = sh.p;
+    g.batch = batch;
+    g.inv_n_out = 1.0f / (float)sh.n_out;
+    const int64_t per_axis = ((int64_t)sh.k + sh.s - 1) / sh.s;          // windows that can cover one pixel, per axis
+    const int64_t column_max = per_axis * per_axis;
+    if (column_max > kCscStage || column_max < kCscTileShortColumn) return c;
+    const int tj_max = (int)std::min<int64_t>(32, kCscStage / column_max);
+    double best = 0.0;
+    for (size_t budget : kCscTileLds) {
+        for (int tj = 1; tj <= tj_max; tj *= 2) {
+            if (tj > 1 && tj / 2 >= sh.n) break;
+            for (int ti = 1; ti <= 64; ti *= 2) {
+                if (ti > 1 && ti / 2 >= sh.m) break;
+                const int64_t wx = std::min<int64_t>(((int64_t)ti + sh.k - 2) / sh.s + 1, sh.m_out);
+                const int64_t wy = std::min<int64_t>(((int64_t)tj + sh.k - 2) / sh.s + 1, sh.n_out);
+                const int64_t limit = (wx - 1) * sh.n_out + wy;
+                if (limit > (1 << 21)) continue;
+                const int64_t stage = (tj * column_max + 1) / 2 * 2, ptrs = ((int64_t)ti * (tj + 1) + 3) / 4 * 4;
+                const int64_t lds = 16 * stage + 4 * ptrs + wx * wy * bc * 4;
+                if (lds > (int64_t)budget) continue;
+                const int64_t tiles_i = (sh.m + ti - 1) / ti, tiles_j = (sh.n + tj - 1) / tj;
+                const int64_t blocks = tiles_i * tiles_j;
+                if (blocks > kInt32Limit) continue;
+                double score = (double)(wx * wy) / ((double)ti * tj);
+                const double work = (double)blocks * chunks * c.waves;
+                if (work < 8192.0) score *= 8192.0 / work;
+                if (!c.ok || score < best) {
+                    c.ok = true;
+                    best = score;
+                    g.ti = ti; g.tj = tj; g.tiles_j = (int)tiles_j;
+                    g.wx = (int)wx; g.wy = (int)wy; g.inv_wy = 1.0f / (float)wy;
+                    g.limit = (int)limit; g.stage = (int)stage; g.ptrs = (int)ptrs;
+                    c.lds = (size_t)lds;
+                    c.grid = dim3((unsigned)blocks, (unsigned)chunks);
+                }
+            }
+        }
+        if (c.ok && best <= kCscTileWindowGoal) break;
+    }
+    c.g = g;
+    return c;
+}
+
+template <int VB, int W>
+static void launch_csc_tile(const CscTileChoice &c, const conv_plan *plan, const float *x_dev, float *y_dev,
+                            hipStream_t q) {
+    spmm_csc_tile_kernel<VB, W><<<c.grid, W * kWave, c.lds, q>>>(plan->row_ptr, plan->col_idx, plan->vals, x_dev, y_dev,
+                                                                 c.g);
+}
+
+extern "C" {
+
 int conv_spmv_from_csc(const conv_plan *plan, const float *x_dev, float *y_dev, int batch, void *stream) {
     if (!plan || !x_dev || !y_dev) return CONV_ENULL;
     if (batch < 1 || !plan->transposed || plan->compact) return CONV_EINVAL;
@@ -864,7 +948,15 @@ int conv_spmv_from_csc(const conv_plan *plan, const float *x_dev, float *y_dev, 
     const long long count = (long long)out_pixels * batch;
     const unsigned fill_blocks = (unsigned)std::min<long long>((count + kGatherThreads - 1) / kGatherThreads, 1 << 16);
     fill_zero_kernel<<<fill_blocks, kGatherThreads, 0, q>>>(y_dev, count);
-    if (plan->nnz > 0) {
+    CscTileChoice tc{};
+    if (plan->nnz > 0) tc = choose_csc_tile(plan, batch);
+    if (tc.ok) {
+        if (tc.vb == 1) launch_csc_tile<1, 1>(tc, plan, x_dev, y_dev, q);
+        else if (tc.vb == 2) launch_csc_tile<2, 1>(tc, plan, x_dev, y_dev, q);
+        else if (tc.waves == 1) launch_csc_tile<4, 1>(tc, plan, x_dev, y_dev, q);
+        else if (tc.waves == 2) launch_csc_tile<4, 2>(tc, plan, x_dev, y_dev, q);
+        else launch_csc_tile<4, 4>(tc, plan, x_dev, y_dev, q);
+    } else if (plan->nnz > 0) {
         const int g = group_width(plan->max_row_nnz);
         const int bl = batch >= 16 ? 16 : (batch >= 4 ? 4 : 1);      // lanes across the batch
         const int64_t blocks = (in_pixels * g * bl + kGatherThreads - 1) / kGatherThreads;

@@ -194,6 +194,12 @@ def test_transposed_march_reads_the_stored_arrays(march_everywhere):
     ((37, 53, 7, 1, 3), 16), ((130, 67, 7, 1, 3), 4), ((100, 90, 5, 2, 2), 8), ((33, 200, 3, 1, 1), 1),
     ((75, 75, 9, 3, 8), 3), ((40, 40, 13, 1, 6), 5), ((6, 6, 2, 1, 5), 7), ((1, 1, 1, 5, 2), 3),
     ((224, 224, 7, 2, 3), 16), ((5, 5, 2, 2, 0), 4), ((300, 301, 2, 2, 0), 12),
+    # batch tails of the four-column lanes and of the sixteen-column pass
+    ((90, 77, 7, 1, 3), 2), ((90, 77, 7, 1, 3), 9), ((90, 77, 7, 1, 3), 17), ((61, 45, 5, 1, 2), 33),
+    # columns no window covers (s > k), one tile line per column (k = 31), beyond the stage (k = 40)
+    ((60, 60, 3, 5, 0), 4), ((70, 70, 31, 1, 15), 3), ((50, 50, 40, 1, 20), 2), ((64, 48, 17, 2, 8), 16),
+    # a few lines of many tiles, many lines of one tile, several full tiles with a ragged rim
+    ((3, 700, 5, 1, 2), 16), ((700, 3, 5, 1, 2), 16), ((515, 509, 7, 1, 3), 16), ((259, 263, 3, 1, 1), 1),
 ])
 def test_product_from_the_csc_arrays_is_the_convolution(shape, batch):
     """y = T x computed by scattering the column-compressed entries (the paper's CSC variant)
@@ -216,6 +222,42 @@ def test_product_from_the_csc_arrays_is_the_convolution(shape, batch):
         assert np.all(got[~live] == 0.0)
         err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
         assert (np.max(err[live] / scale[live]) if np.any(live) else 0.0) <= 1e-5
+    plan.close()
+
+
+def test_product_from_csc_reads_the_stored_arrays():
+    """The scatter uses the stored row indices and values, wherever they point: one entry of a
+    column is sent to a row far from the pixel's windows (outside what the workgroup keeps on
+    chip) and one value is changed; the result must be the product with that edited matrix."""
+    import scipy.sparse as sp
+    shape, batch = (96, 80, 7, 1, 3), 16
+    m, n, k, s, p = shape
+    rng = np.random.default_rng(29)
+    x = rng.standard_normal(m * n * batch).astype(np.float32)
+    K = rng.standard_normal(k * k).astype(np.float32)
+    plan = build_plan_t(shape, K)
+    cp, ri, va = oracle.csc(m, n, k, s, p, K)
+    col = 40 * n + 9
+    e = int(cp[col]) + 5
+    far = plan.cols - 1                       # the last output: not among this column's rows
+    assert far not in ri[cp[col]:cp[col + 1]]
+    ri2, va2 = ri.copy(), va.copy()
+    ri2[e] = far
+    va2[e + 1] = 3.5
+    plan.col_idx[e] = far
+    plan.vals[e + 1] = 3.5
+    y = cs.conv_spmv_from_csc(plan, torch.from_numpy(x).to(device()), batch=batch)
+    torch.cuda.synchronize()
+    T = sp.csc_matrix((va2.astype(np.float64), ri2, cp), shape=(plan.cols, plan.rows))
+    X = x.reshape(-1, batch).astype(np.float64)
+    want = T @ X
+    scale = abs(T) @ np.abs(X)
+    got = y.cpu().numpy().reshape(-1, batch)
+    assert np.all(np.abs(got - want) <= 1e-5 * scale + 1e-30)
+    # the edit is visible: the far row and the row the entry left both differ from the unedited product
+    ref = oracle.conv(m, n, k, s, p, x, K, batch=batch).reshape(-1, batch)
+    changed = np.where(np.any(np.abs(got - ref) > 1e-5 * scale + 1e-30, axis=1))[0].tolist()
+    assert far in changed and int(ri[e]) in changed and int(ri[e + 1]) in changed
     plan.close()
 
 
