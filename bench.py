@@ -414,6 +414,18 @@ def main():
             side[tag] = {"kernel": pl.variant(w.batch), "kernel_ms_avg": avg, "model_bytes": pl.model_bytes(w.batch),
                          "model_gbs": pl.model_bytes(w.batch) / (avg * 1e-3) / 1e9,
                          "useful_tflops": 2.0 * pl.nnz * w.batch / (avg * 1e-3) / 1e12}
+            if tag == "transposed_csc":
+                # y = T x from the same column-compressed arrays (a scatter: zero fill + sums per tile)
+                for _ in range(10):
+                    cs.conv_spmv_from_csc(pl, x, y, batch=w.batch)
+                torch.cuda.synchronize()
+                for a, b in pairs:
+                    a.record(stream)
+                    cs.conv_spmv_from_csc(pl, x, y, batch=w.batch)
+                    b.record(stream)
+                torch.cuda.synchronize()
+                avg = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
+                side["product_from_csc"] = {"ms_avg": avg, "useful_tflops": 2.0 * pl.nnz * w.batch / (avg * 1e-3) / 1e12}
             pl.close()
         out["side_paths"] = side
     if not args.no_cpu:
