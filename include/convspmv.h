@@ -171,9 +171,9 @@ int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream);
  * product with whatever the three arrays hold, provided row_ptr is still
  * non-decreasing with row lengths <= k*k and every col_idx is in [0, m*n).
  * fp32 multiply-add, summation order unspecified but fixed: repeated calls
- * give bit-identical results.  (A plan with several channels may run one
- * kernel per channel on `stream`, the later ones adding to y with one
- * hardware float add per element; the order of those adds is the launch
+ * give bit-identical results.  (A plan with several channels runs either
+ * one kernel that sums the channels in a fixed order, or one kernel per
+ * channel on `stream`, the later ones adding to y once per element in launch
  * order.)  x and y must not overlap. */
 int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch, void *stream);
 
@@ -216,12 +216,13 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch);
  * CONV_ENULL).  For tests of the host logic and for reports. */
 typedef struct conv_dispatch {
     int kernel;             /* 0 row-group scalar, 1 row-group float4, 2 LDS tile, 3 LDS march,
-                               4 described rows (structure-aware), 5 rectangle path (structure-aware) */
+                               4 described rows (structure-aware), 5 rectangle path (structure-aware),
+                               6 all channels in one launch, 8 x 8 outputs per wave (structure-aware) */
     int threads;            /* per workgroup */
     int64_t lds_bytes;      /* dynamic LDS per workgroup */
     int64_t workgroups;     /* that do work, over the whole launch (per channel for kernel 3) */
-    int strip;              /* output columns per strip / tile line (kernels 2-5), else 0 */
-    int segment;            /* output lines per workgroup (kernels 2-5), else 0 */
+    int strip;              /* output columns per strip / tile line (kernels 2-6), else 0 */
+    int segment;            /* output lines per workgroup (kernels 2-6), else 0 */
     int ring_lines;         /* LDS ring lines (kernels 3-5; 0 = no ring) */
     int ring_lines_needed;  /* lines a step keeps resident (<= ring_lines when there is a ring) */
     int lines_per_step;     /* output lines per step (kernels 3-5) */

@@ -185,11 +185,6 @@ __device__ __forceinline__ int first_window(int t0, int k, int s, int p) {   // 
     return num <= 0 ? 0 : (int)((num + s - 1) / s);
 }
 
-__device__ __forceinline__ void wave_lds_order() {    // later LDS accesses of this wave stay behind earlier ones
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
 template <int VB, int W>
 __global__ __launch_bounds__(W *kWave) void spmm_csc_tile_kernel(
     const int *__restrict__ col_ptr, const int *__restrict__ row_idx, const float *__restrict__ vals,

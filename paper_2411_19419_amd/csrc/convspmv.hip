@@ -14,6 +14,7 @@
 #include "apply_march_kernel.h"
 #include "apply_tile_kernel.h"
 #include "build_kernels.h"
+#include "compact_channels_kernel.h"
 #include "compact_kernels.h"
 
 using namespace convspmv;
@@ -742,6 +743,86 @@ CompactChoice choose_compact(const conv_plan *plan, const float *x, const float 
     return c;
 }
 
+// Several channels in one launch (compact_channels_kernel.h): when the channels are many and a
+// channel's product is short, so that one launch per channel would be bound by launches and by
+// re-reading y.  VB batch columns per lane (16, 8 or 4, dividing the batch) and W = 4 or 8
+// waves per workgroup that split the channels: the widest VB whose launch has kChanFusedWaves
+// waves with the most ways that fit LDS and the channel count, else the shape with most waves.
+constexpr double kChanFusedWork = 1e8;        // multiply-adds per channel below which the launches are fused
+constexpr int64_t kChanFusedWaves = 2048;     // waves that fill the chip (8 per CU)
+
+struct ChannelsChoice {
+    bool ok;
+    int vb, ways;
+    size_t lds;
+    dim3 grid;
+    CompactChannelsGeom geom;
+};
+
+ChannelsChoice choose_compact_channels(const conv_plan *plan, const float *x, const float *y, int batch) {
+    const ConvShape &sh = plan->shape;
+    ChannelsChoice c{};
+    if (!plan->compact || plan->channels < kChanMinWaves || batch % 4) return c;
+    if (((((uintptr_t)x) | ((uintptr_t)y)) & 15u) != 0) return c;
+    if ((double)plan->nnz * batch > kChanFusedWork) return c;
+    // int arithmetic in the kernel: s*x - p + k over the padded plane, float offsets within a channel's plane
+    if ((int64_t)sh.m + 2LL * sh.p + sh.k + 8LL * sh.s >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + sh.k + 8LL * sh.s >= (1LL << 30) ||
+        (int64_t)sh.m * sh.n * batch >= kInt32Limit)
+        return c;
+    const int64_t ph = (int64_t)(kChanTile - 1) * sh.s + sh.k;
+    const int64_t tiles_x = (sh.m_out + kChanTile - 1) / kChanTile, tiles_y = (sh.n_out + kChanTile - 1) / kChanTile;
+    if (tiles_x * tiles_y > kInt32Limit) return c;
+    int64_t best_waves = 0;
+    for (int vb = batch % 16 == 0 ? 16 : (batch % 8 == 0 ? 8 : 4); vb >= 4; vb /= 2) {
+        if (ph * ph * (vb / 4) > (int64_t)kChanItems * kWave || batch / vb > 65535) continue;
+        const int64_t vec4 = std::max<int64_t>(ph * ph, kWave) * (vb / 4) + ((int64_t)sh.k * sh.k + 3) / 4;
+        int ways = kChanMinWaves;
+        while (ways < kChanMaxWaves && 2 * ways <= plan->channels && vec4 * 16 * 2 * ways <= 64 * 1024) ways *= 2;
+        if (vec4 * 16 * ways > 64 * 1024) continue;
+        const int64_t blocks = tiles_x * tiles_y * (batch / vb);
+        while (ways > kChanMinWaves && blocks * (ways / 2) >= kChanFusedWaves) ways /= 2;     // no more ways than the chip needs
+        const int64_t waves = blocks * ways;
+        if (c.ok && waves <= best_waves) continue;
+        best_waves = waves;
+        c.ok = true;
+        c.vb = vb;
+        c.ways = ways;
+        c.lds = (size_t)(vec4 * 16 * ways);
+        c.grid = dim3((unsigned)(tiles_x * tiles_y), (unsigned)(batch / vb));
+        CompactChannelsGeom g{};
+        g.m = sh.m; g.n = sh.n; g.m_out = sh.m_out; g.n_out = sh.n_out; g.s = sh.s; g.p = sh.p; g.k = sh.k;
+        g.batch = batch; g.channels = plan->channels;
+        g.tiles_y = (int)tiles_y;
+        g.ph = (int)ph;
+        g.wave_vec4 = (int)vec4;
+        g.inv_ph = 1.0f / (float)ph;
+        g.plane = (long long)sh.m * sh.n * batch;
+        c.geom = g;
+        if (waves >= kChanFusedWaves) break;
+    }
+    return c;
+}
+
+template <int VB>
+void launch_compact_channels_vb(const ChannelsChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    const int threads = c.ways * kWave;
+    const int per_lane = (c.geom.ph * c.geom.ph * (VB / 4) + kWave - 1) / kWave;      // patch items a lane carries
+    if (per_lane <= 4)
+        spmm_compact_channels_kernel<VB, 4><<<c.grid, threads, c.lds, q>>>(plan->desc, plan->ktab, x, y, c.geom);
+    else if (per_lane <= 8)
+        spmm_compact_channels_kernel<VB, 8><<<c.grid, threads, c.lds, q>>>(plan->desc, plan->ktab, x, y, c.geom);
+    else
+        spmm_compact_channels_kernel<VB, kChanItems><<<c.grid, threads, c.lds, q>>>(plan->desc, plan->ktab, x, y, c.geom);
+}
+
+void launch_compact_channels(const ChannelsChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    switch (c.vb) {
+        case 16: launch_compact_channels_vb<16>(c, plan, x, y, q); break;
+        case 8: launch_compact_channels_vb<8>(c, plan, x, y, q); break;
+        default: launch_compact_channels_vb<4>(c, plan, x, y, q); break;
+    }
+}
+
 template <int KK, int SS, int LPR, bool SCALAR, bool ACC>
 bool launch_compact_one(const CompactChoice &c, const CompactGeom &g, const conv_plan *plan, const float *ktab,
                         const float *x, float *y, dim3 grid, hipStream_t q) {
@@ -817,6 +898,11 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
     }
     hipStream_t q = (hipStream_t)stream;
     if (plan->compact) {
+        const ChannelsChoice fused = choose_compact_channels(plan, x_dev, y_dev, batch);
+        if (fused.ok) {
+            launch_compact_channels(fused, plan, x_dev, y_dev, q);
+            return hip_ok(hipGetLastError()) ? CONV_OK : CONV_EHIP;
+        }
         const CompactChoice cc = choose_compact(plan, x_dev, y_dev, batch);
         if (!cc.ok) return CONV_EOVERFLOW;
         if (!launch_compact(cc, plan, x_dev, y_dev, q)) return CONV_EHIP;
@@ -1114,7 +1200,16 @@ int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage
     const int per_axis = plan.transposed ? (k + s - 1) / s : k;
     plan.max_row_nnz = per_axis * per_axis;
     conv_dispatch d{};
-    if (plan.compact) {
+    const ChannelsChoice fused = choose_compact_channels(&plan, nullptr, nullptr, batch);
+    if (fused.ok) {
+        d.kernel = 6;
+        d.threads = fused.ways * kWave;
+        d.lds_bytes = (int64_t)fused.lds;
+        d.strip = d.segment = kChanTile;
+        d.lanes_per_row = 1;
+        d.columns_per_lane = fused.vb;
+        d.workgroups = (int64_t)fused.grid.x * fused.grid.y;
+    } else if (plan.compact) {
         const CompactChoice cc = choose_compact(&plan, nullptr, nullptr, batch);
         if (!cc.ok) return CONV_EOVERFLOW;
         d.kernel = cc.kk ? 5 : 4;
@@ -1159,6 +1254,12 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch) {
     if (!plan || batch < 1) return nullptr;
     static thread_local char name[96];
     if (plan->compact) {
+        const ChannelsChoice fused = choose_compact_channels(plan, nullptr, nullptr, batch);
+        if (fused.ok) {
+            snprintf(name, sizeof name, "compact_channels_%dx%d_float4x%d_%d_ways_%d_channels", kChanTile, kChanTile,
+                     fused.vb / 4, fused.ways, plan->channels);
+            return name;
+        }
         const CompactChoice cc = choose_compact(plan, nullptr, nullptr, batch);
         if (!cc.ok) return nullptr;
         char cols[16];

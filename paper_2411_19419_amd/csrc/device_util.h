@@ -43,23 +43,12 @@ __device__ __forceinline__ int div_small(int a, float inv) {
     return (int)(((float)a + 0.5f) * inv);
 }
 
-// floor(a / d) for 0 <= a < 2^31 and d >= 1 by one widening multiplication: with l =
-// ceil(log2 d) and mul = floor(2^(31+l) / d) + 1 (at most 2^32 - 1 for d >= 2, 2^31 + 1 for
-// d = 1), a * mul / 2^(31+l) exceeds a/d by less than 2^-l <= 1/d, which cannot carry the
-// value past the next integer because the fraction of a/d is at most (d-1)/d.
-struct DivMagic {
-    unsigned mul;
-    int shift;      // 31 + l
-};
-
-inline DivMagic div_magic(int d) {
-    int l = 0;
-    while ((1ll << l) < d) ++l;
-    return DivMagic{(unsigned)(((1ull << (31 + l)) / (unsigned)d) + 1ull), 31 + l};
-}
-
-__device__ __forceinline__ int div_by(int a, DivMagic d) {
-    return (int)(((unsigned long long)(unsigned)a * d.mul) >> d.shift);
+// Where the lanes of one wave hand data to each other through LDS without a workgroup barrier
+// (the LDS instructions of a wave execute in order): later LDS accesses of this wave stay
+// behind earlier ones, for the compiler too.
+__device__ __forceinline__ void wave_lds_order() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 }
 
 }  // namespace convspmv

@@ -115,6 +115,12 @@ def test_channel_errors():
     ((37, 53, 7, 1, 3), 3, 16), ((130, 67, 7, 1, 3), 2, 4), ((100, 90, 5, 2, 2), 4, 8), ((33, 200, 3, 1, 1), 8, 1),
     ((75, 75, 9, 3, 8), 2, 3), ((6, 6, 2, 1, 5), 5, 7), ((224, 224, 7, 2, 3), 3, 16), ((56, 56, 3, 1, 1), 64, 4),
     ((64, 64, 3, 1, 1), 1, 16), ((300, 301, 2, 2, 0), 2, 12),
+    # all channels in one launch (four or more channels, batch a multiple of 4): channel counts that do
+    # and do not divide among the four waves, 4, 8 and 16 batch columns per lane, ragged tiles, strides,
+    # k = 1, a patch that only fits with 4 columns per lane, tiles that lie wholly in the padding
+    ((56, 56, 3, 1, 1), 64, 16), ((61, 43, 3, 1, 1), 5, 16), ((61, 43, 5, 2, 2), 7, 8), ((37, 53, 7, 1, 3), 4, 32),
+    ((28, 28, 1, 1, 0), 9, 16), ((40, 45, 7, 2, 3), 6, 16), ((30, 30, 13, 1, 6), 4, 16), ((7, 7, 3, 1, 1), 33, 4),
+    ((20, 22, 3, 1, 12), 4, 16), ((33, 31, 4, 3, 5), 5, 12), ((112, 112, 3, 2, 1), 16, 16),
 ])
 def test_channel_sum_from_the_structure_aware_storage(shape, channels, batch):
     m, n, k, s, p = shape
@@ -141,4 +147,58 @@ def test_channel_sum_from_the_structure_aware_storage(shape, channels, batch):
     ref2, scale2 = oracle.conv_channels(m, n, k, s, p, x, K2, channels, batch=batch, want_scale=True)
     err2 = np.abs(y3.cpu().numpy().astype(np.float64) - ref2.astype(np.float64))
     assert (np.max(err2[scale2 > 0] / scale2[scale2 > 0]) if np.any(scale2 > 0) else 0.0) <= REL_TOL
+    plan.close()
+
+
+def test_channels_in_one_launch_is_what_runs():
+    m, n, k, s, p = 56, 56, 3, 1, 1
+    K = torch.zeros(8 * k * k, device=device())
+    plan = cs.conv_compact_build(m, n, k, s, p, K, channels=8)
+    # 49 tiles: every batch gets the narrowest lanes (most workgroups) and all eight ways
+    assert plan.variant(16) == "compact_channels_8x8_float4x1_8_ways_8_channels"
+    assert plan.variant(12) == "compact_channels_8x8_float4x1_8_ways_8_channels"
+    assert plan.variant(3).startswith("compact_rect")          # batch not a multiple of 4: one launch per channel
+    plan.close()
+    plan = cs.conv_compact_build(m, n, k, s, p, K[:3 * k * k], channels=3)
+    assert plan.variant(16).startswith("compact_rect")         # fewer channels than waves
+    plan.close()
+    plan = cs.conv_compact_build(1024, 1024, 7, 1, 3, torch.zeros(4 * 49, device=device()), channels=4)
+    assert plan.variant(16).startswith("compact_rect")         # long products: a launch per channel is no burden
+    plan.close()
+
+
+def test_channels_in_one_launch_follow_edited_descriptors():
+    """The one-launch kernel sums full k x k windows over a zero-padded patch only where the
+    descriptors are the ones Theorem 2.1 gives; a wave that reads any other descriptor walks the
+    described rectangles.  Rows are edited (a rectangle made smaller, one moved to another place
+    of the image, one row emptied) and the result is compared with scipy on the decoded matrices."""
+    import scipy.sparse as sp
+    shape, channels, batch = (40, 45, 5, 1, 2), 6, 16
+    m, n, k, s, p = shape
+    x, K = _case(shape, channels, batch, 41)
+    plan = cs.conv_compact_build(m, n, k, s, p, torch.from_numpy(K).to(device()), channels=channels)
+    assert plan.variant(batch).startswith("compact_channels")
+    desc = oracle.compact_rows(m, n, k, s, p).copy()
+    mo, no = oracle.out_shape(m, n, k, s, p)
+    r_small, r_moved, r_empty = 10 * no + 12, 25 * no + 30, 3 * no + 3
+    desc[r_small, 1] = 1 | 2 << 8 | 0 << 16 | 3 << 24          # taps (1..2, 0..2) from the same first column
+    desc[r_moved, 0] = 2 * n + 1                                # the full window, read from the image's corner
+    desc[r_empty] = (0, 0)
+    plan.row_desc.copy_(torch.from_numpy(desc).to(device()))
+    y = cs.conv_spmv(plan, torch.from_numpy(x).to(device()), batch=batch)
+    torch.cuda.synchronize()
+    X = x.reshape(channels, m * n, batch).astype(np.float64)
+    want = np.zeros((mo * no, batch))
+    scale = np.zeros((mo * no, batch))
+    for ch in range(channels):
+        rp, ci, va = oracle.compact_decode(n, k, desc, K[ch * k * k:(ch + 1) * k * k])
+        T = sp.csr_matrix((va.astype(np.float64), ci, rp), shape=(mo * no, m * n))
+        want += T @ X[ch]
+        scale += abs(T) @ np.abs(X[ch])
+    got = y.cpu().numpy().reshape(-1, batch)
+    assert np.all(got[r_empty] == 0.0)
+    assert np.all(np.abs(got - want) <= REL_TOL * scale + 1e-30)
+    ref = oracle.conv_channels(m, n, k, s, p, x, K, channels, batch=batch).reshape(-1, batch)
+    changed = np.where(np.any(np.abs(got - ref) > REL_TOL * scale + 1e-30, axis=1))[0].tolist()
+    assert set(changed) == {r_small, r_moved, r_empty}
     plan.close()

@@ -222,6 +222,36 @@ def test_dispatch_geometry_is_consistent_over_many_shapes():
     assert seen == {0, 1, 2, 3, 4, 5}
 
 
+def test_dispatch_of_channel_sums_from_the_structure_aware_storage():
+    """All channels in one launch when they are at least four, the batch is a multiple of 4 and a
+    channel's product is short; otherwise the per-channel kernels.  LDS of the four waves' patches
+    of (7 s + k)^2 pixels within 64 KiB, fewer batch columns per lane when they would not fit."""
+    d = _dispatch(224, 224, 3, 1, 1, 16, 2, 64)                          # 784 tiles: full lines per lane, 4 ways
+    assert d["kernel"] == 6 and d["threads"] == 256 and d["columns_per_lane"] == 16
+    assert d["workgroups"] == 28 * 28 and d["strip"] == d["segment"] == 8
+    assert d["lds_bytes"] == 4 * 16 * (10 * 10 * 4 + 3)
+    d = _dispatch(56, 56, 3, 1, 1, 16, 2, 64)                            # 49 tiles: narrow lanes, 8 ways
+    assert d["kernel"] == 6 and d["threads"] == 512 and d["columns_per_lane"] == 4 and d["workgroups"] == 49 * 4
+    assert _dispatch(224, 224, 3, 1, 1, 32, 2, 64)["workgroups"] == 28 * 28 * 2
+    assert _dispatch(224, 224, 3, 1, 1, 8, 2, 64)["columns_per_lane"] == 8
+    assert _dispatch(224, 224, 3, 1, 1, 20, 2, 64)["columns_per_lane"] == 4
+    assert _dispatch(56, 56, 3, 1, 1, 6, 2, 64)["kernel"] == 5          # batch not a multiple of 4
+    assert _dispatch(56, 56, 3, 1, 1, 16, 2, 3)["kernel"] == 5          # fewer channels than waves
+    assert _dispatch(1024, 1024, 7, 1, 3, 16, 2, 64)["kernel"] == 5     # long products
+    d = _dispatch(150, 150, 13, 1, 6, 16, 2, 8)                          # 20 x 20 patch: 16 columns per lane do not fit
+    assert d["kernel"] == 6 and d["columns_per_lane"] == 8 and d["lds_bytes"] <= 64 * 1024
+    assert _dispatch(100, 100, 40, 1, 20, 16, 2, 8)["kernel"] == 4      # 47 x 47 patch: no fit, described rows
+    for k, s in ((1, 1), (3, 1), (3, 2), (5, 1), (7, 2), (9, 3), (11, 1)):
+        for batch in (4, 8, 12, 16, 64):
+            for channels in (4, 12, 100):
+                d = _dispatch(112, 96, k, s, k // 2, batch, 2, channels)
+                assert d["kernel"] == 6 and d["lds_bytes"] <= 64 * 1024 and batch % d["columns_per_lane"] == 0
+                assert d["threads"] in (256, 512) and d["threads"] // 64 <= channels
+                assert d["workgroups"] * d["columns_per_lane"] >= batch
+                patch = (7 * s + k) ** 2 * d["columns_per_lane"] // 4
+                assert patch <= 16 * 64 and d["lds_bytes"] >= d["threads"] // 64 * 16 * patch
+
+
 def test_dispatch_of_the_named_workloads():
     want = {"small_32_k3": 0, "strided_256_k5_b64": 2, "headline_1024_k7_b1": 3, "headline_1024_k7_b16": 3,
             "cnn_224_k3_b256": 2, "padheavy_512_k9_s3": 0, "padheavy_4096_k11_s4_b4": 3}
