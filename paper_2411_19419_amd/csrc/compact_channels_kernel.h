@@ -31,6 +31,7 @@ struct CompactChannelsGeom {
     int m, n, m_out, n_out, s, p, k;
     int batch, channels;
     int tiles_y;          // tiles per line of tiles
+    int tiles, tiles_per_xcd;
     int ph;               // patch side in pixels: 7 s + k
     int wave_vec4;        // float4 of LDS per wave: patch (or one partial sum per lane) + the channel's table
     float inv_ph;
@@ -50,8 +51,10 @@ __device__ __forceinline__ int2 described_by_position(int m, int n, int k, int s
     return d;
 }
 
-// VB batch columns per lane; NI float4 of a patch per lane (at least (7 s + k)^2 VB / 256).
-template <int VB, int NI>
+// VB batch columns per lane; NI float4 of a patch per lane (at least (7 s + k)^2 VB / 256); KK: the
+// kernel size the tap loops are unrolled for, with the channel's table in scalar registers (0: any
+// k, table in LDS).
+template <int VB, int NI, int KK>
 __global__ __launch_bounds__(kChanMaxWaves *kWave) void spmm_compact_channels_kernel(
     const int2 *__restrict__ desc, const float *__restrict__ ktab, const float *__restrict__ x, float *__restrict__ y,
     const CompactChannelsGeom g) {
@@ -64,7 +67,11 @@ __global__ __launch_bounds__(kChanMaxWaves *kWave) void spmm_compact_channels_ke
     const int ways = (int)blockDim.x / kWave;
     float4 *const patch = chan_lds + wave * g.wave_vec4;
     float *const table = reinterpret_cast<float *>(patch + max(g.ph * g.ph, kWave) * Q);
-    const int tile_x = (int)blockIdx.x / g.tiles_y, tile_y = (int)blockIdx.x - tile_x * g.tiles_y;
+    // consecutive workgroups go to different XCDs; a band of neighbouring tiles to one, so that the pixels
+    // two tiles share are fetched into one L2
+    const int tile = ((int)blockIdx.x % kXcds) * g.tiles_per_xcd + (int)blockIdx.x / kXcds;
+    if ((int)blockIdx.x / kXcds >= g.tiles_per_xcd || tile >= g.tiles) return;      // uniform over the workgroup
+    const int tile_x = tile / g.tiles_y, tile_y = tile - tile_x * g.tiles_y;
     const int lx = lane / kChanTile, ly = lane % kChanTile;
     const int ox = tile_x * kChanTile + lx, oy = tile_y * kChanTile + ly;
     const bool live = ox < g.m_out && oy < g.n_out;
@@ -114,16 +121,34 @@ __global__ __launch_bounds__(kChanMaxWaves *kWave) void spmm_compact_channels_ke
             for (int u = 0; u < NI; ++u)
                 if (u * kWave < items && u * kWave + lane < items)
                     patch[u * kWave + lane] = at[u] >= 0 ? next[u] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            for (int t = lane; t < kk; t += kWave) table[t] = ktab[(long long)c * kk + t];
-            ask(c + ways);
-            wave_lds_order();
-            for (int a = 0; a < g.k; ++a) {
-                const float4 *line = mine + a * g.ph * Q;
-                const float *tl = table + a * g.k;
-                for (int b = 0; b < g.k; ++b) {
-                    const float w = tl[b];
+            if constexpr (KK > 0) {
+                float w[KK * KK];               // the same for every lane: scalar loads, scalar operands
+                const float *tc = ktab + (long long)c * (KK * KK);
 #pragma unroll
-                    for (int q = 0; q < Q; ++q) fma4(acc[q], w, line[b * Q + q]);
+                for (int t = 0; t < KK * KK; ++t) w[t] = tc[t];
+                ask(c + ways);
+                wave_lds_order();
+#pragma unroll
+                for (int a = 0; a < KK; ++a) {
+                    const float4 *line = mine + a * g.ph * Q;
+#pragma unroll
+                    for (int b = 0; b < KK; ++b) {
+#pragma unroll
+                        for (int q = 0; q < Q; ++q) fma4(acc[q], w[a * KK + b], line[b * Q + q]);
+                    }
+                }
+            } else {
+                for (int t = lane; t < kk; t += kWave) table[t] = ktab[(long long)c * kk + t];
+                ask(c + ways);
+                wave_lds_order();
+                for (int a = 0; a < g.k; ++a) {
+                    const float4 *line = mine + a * g.ph * Q;
+                    const float *tl = table + a * g.k;
+                    for (int b = 0; b < g.k; ++b) {
+                        const float w = tl[b];
+#pragma unroll
+                        for (int q = 0; q < Q; ++q) fma4(acc[q], w, line[b * Q + q]);
+                    }
                 }
             }
             wave_lds_order();

@@ -762,7 +762,7 @@ struct ChannelsChoice {
 ChannelsChoice choose_compact_channels(const conv_plan *plan, const float *x, const float *y, int batch) {
     const ConvShape &sh = plan->shape;
     ChannelsChoice c{};
-    if (!plan->compact || plan->channels < kChanMinWaves || batch % 4) return c;
+    if (!plan->compact || plan->channels < 2 || batch % 4) return c;
     if (((((uintptr_t)x) | ((uintptr_t)y)) & 15u) != 0) return c;
     if ((double)plan->nnz * batch > kChanFusedWork) return c;
     // int arithmetic in the kernel: s*x - p + k over the padded plane, float offsets within a channel's plane
@@ -771,7 +771,7 @@ ChannelsChoice choose_compact_channels(const conv_plan *plan, const float *x, co
         return c;
     const int64_t ph = (int64_t)(kChanTile - 1) * sh.s + sh.k;
     const int64_t tiles_x = (sh.m_out + kChanTile - 1) / kChanTile, tiles_y = (sh.n_out + kChanTile - 1) / kChanTile;
-    if (tiles_x * tiles_y > kInt32Limit) return c;
+    if (tiles_x * tiles_y + kXcds > kInt32Limit) return c;
     int64_t best_waves = 0;
     for (int vb = batch % 16 == 0 ? 16 : (batch % 8 == 0 ? 8 : 4); vb >= 4; vb /= 2) {
         if (ph * ph * (vb / 4) > (int64_t)kChanItems * kWave || batch / vb > 65535) continue;
@@ -788,8 +788,11 @@ ChannelsChoice choose_compact_channels(const conv_plan *plan, const float *x, co
         c.vb = vb;
         c.ways = ways;
         c.lds = (size_t)(vec4 * 16 * ways);
-        c.grid = dim3((unsigned)(tiles_x * tiles_y), (unsigned)(batch / vb));
+        const int64_t per_xcd = (tiles_x * tiles_y + kXcds - 1) / kXcds;
+        c.grid = dim3((unsigned)(per_xcd * kXcds), (unsigned)(batch / vb));
         CompactChannelsGeom g{};
+        g.tiles = (int)(tiles_x * tiles_y);
+        g.tiles_per_xcd = (int)per_xcd;
         g.m = sh.m; g.n = sh.n; g.m_out = sh.m_out; g.n_out = sh.n_out; g.s = sh.s; g.p = sh.p; g.k = sh.k;
         g.batch = batch; g.channels = plan->channels;
         g.tiles_y = (int)tiles_y;
@@ -803,16 +806,26 @@ ChannelsChoice choose_compact_channels(const conv_plan *plan, const float *x, co
     return c;
 }
 
-template <int VB>
-void launch_compact_channels_vb(const ChannelsChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+template <int VB, int KK>
+void launch_compact_channels_k(const ChannelsChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
     const int threads = c.ways * kWave;
     const int per_lane = (c.geom.ph * c.geom.ph * (VB / 4) + kWave - 1) / kWave;      // patch items a lane carries
     if (per_lane <= 4)
-        spmm_compact_channels_kernel<VB, 4><<<c.grid, threads, c.lds, q>>>(plan->desc, plan->ktab, x, y, c.geom);
+        spmm_compact_channels_kernel<VB, 4, KK><<<c.grid, threads, c.lds, q>>>(plan->desc, plan->ktab, x, y, c.geom);
     else if (per_lane <= 8)
-        spmm_compact_channels_kernel<VB, 8><<<c.grid, threads, c.lds, q>>>(plan->desc, plan->ktab, x, y, c.geom);
+        spmm_compact_channels_kernel<VB, 8, KK><<<c.grid, threads, c.lds, q>>>(plan->desc, plan->ktab, x, y, c.geom);
     else
-        spmm_compact_channels_kernel<VB, kChanItems><<<c.grid, threads, c.lds, q>>>(plan->desc, plan->ktab, x, y, c.geom);
+        spmm_compact_channels_kernel<VB, kChanItems, KK><<<c.grid, threads, c.lds, q>>>(plan->desc, plan->ktab, x, y, c.geom);
+}
+
+template <int VB>
+void launch_compact_channels_vb(const ChannelsChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    switch (c.geom.k) {       // the kernel sizes of the paper's layer table (Table 2) have unrolled tap loops
+        case 1: launch_compact_channels_k<VB, 1>(c, plan, x, y, q); break;
+        case 3: launch_compact_channels_k<VB, 3>(c, plan, x, y, q); break;
+        case 7: launch_compact_channels_k<VB, 7>(c, plan, x, y, q); break;
+        default: launch_compact_channels_k<VB, 0>(c, plan, x, y, q); break;
+    }
 }
 
 void launch_compact_channels(const ChannelsChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
@@ -1208,7 +1221,7 @@ int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage
         d.strip = d.segment = kChanTile;
         d.lanes_per_row = 1;
         d.columns_per_lane = fused.vb;
-        d.workgroups = (int64_t)fused.grid.x * fused.grid.y;
+        d.workgroups = (int64_t)fused.geom.tiles * fused.grid.y;
     } else if (plan.compact) {
         const CompactChoice cc = choose_compact(&plan, nullptr, nullptr, batch);
         if (!cc.ok) return CONV_EOVERFLOW;

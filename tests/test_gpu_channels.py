@@ -115,7 +115,7 @@ def test_channel_errors():
     ((37, 53, 7, 1, 3), 3, 16), ((130, 67, 7, 1, 3), 2, 4), ((100, 90, 5, 2, 2), 4, 8), ((33, 200, 3, 1, 1), 8, 1),
     ((75, 75, 9, 3, 8), 2, 3), ((6, 6, 2, 1, 5), 5, 7), ((224, 224, 7, 2, 3), 3, 16), ((56, 56, 3, 1, 1), 64, 4),
     ((64, 64, 3, 1, 1), 1, 16), ((300, 301, 2, 2, 0), 2, 12),
-    # all channels in one launch (four or more channels, batch a multiple of 4): channel counts that do
+    # all channels in one launch (several channels, batch a multiple of 4): channel counts that do
     # and do not divide among the four waves, 4, 8 and 16 batch columns per lane, ragged tiles, strides,
     # k = 1, a patch that only fits with 4 columns per lane, tiles that lie wholly in the padding
     ((56, 56, 3, 1, 1), 64, 16), ((61, 43, 3, 1, 1), 5, 16), ((61, 43, 5, 2, 2), 7, 8), ((37, 53, 7, 1, 3), 4, 32),
@@ -160,7 +160,10 @@ def test_channels_in_one_launch_is_what_runs():
     assert plan.variant(3).startswith("compact_rect")          # batch not a multiple of 4: one launch per channel
     plan.close()
     plan = cs.conv_compact_build(m, n, k, s, p, K[:3 * k * k], channels=3)
-    assert plan.variant(16).startswith("compact_rect")         # fewer channels than waves
+    assert plan.variant(16) == "compact_channels_8x8_float4x1_4_ways_3_channels"      # the fourth wave idles
+    plan.close()
+    plan = cs.conv_compact_build(m, n, k, s, p, K[:k * k])
+    assert plan.variant(16).startswith("compact_rect")         # one channel: nothing to sum
     plan.close()
     plan = cs.conv_compact_build(1024, 1024, 7, 1, 3, torch.zeros(4 * 49, device=device()), channels=4)
     assert plan.variant(16).startswith("compact_rect")         # long products: a launch per channel is no burden

@@ -223,7 +223,7 @@ def test_dispatch_geometry_is_consistent_over_many_shapes():
 
 
 def test_dispatch_of_channel_sums_from_the_structure_aware_storage():
-    """All channels in one launch when they are at least four, the batch is a multiple of 4 and a
+    """All channels in one launch when there are several, the batch is a multiple of 4 and a
     channel's product is short; otherwise the per-channel kernels.  LDS of the four waves' patches
     of (7 s + k)^2 pixels within 64 KiB, fewer batch columns per lane when they would not fit."""
     d = _dispatch(224, 224, 3, 1, 1, 16, 2, 64)                          # 784 tiles: full lines per lane, 4 ways
@@ -236,7 +236,8 @@ def test_dispatch_of_channel_sums_from_the_structure_aware_storage():
     assert _dispatch(224, 224, 3, 1, 1, 8, 2, 64)["columns_per_lane"] == 8
     assert _dispatch(224, 224, 3, 1, 1, 20, 2, 64)["columns_per_lane"] == 4
     assert _dispatch(56, 56, 3, 1, 1, 6, 2, 64)["kernel"] == 5          # batch not a multiple of 4
-    assert _dispatch(56, 56, 3, 1, 1, 16, 2, 3)["kernel"] == 5          # fewer channels than waves
+    assert _dispatch(56, 56, 3, 1, 1, 16, 2, 3)["threads"] == 256       # fewer channels than waves: the fourth idles
+    assert _dispatch(56, 56, 3, 1, 1, 16, 2, 1)["kernel"] == 5          # one channel: nothing to sum
     assert _dispatch(1024, 1024, 7, 1, 3, 16, 2, 64)["kernel"] == 5     # long products
     d = _dispatch(150, 150, 13, 1, 6, 16, 2, 8)                          # 20 x 20 patch: 16 columns per lane do not fit
     assert d["kernel"] == 6 and d["columns_per_lane"] == 8 and d["lds_bytes"] <= 64 * 1024
@@ -246,7 +247,7 @@ def test_dispatch_of_channel_sums_from_the_structure_aware_storage():
             for channels in (4, 12, 100):
                 d = _dispatch(112, 96, k, s, k // 2, batch, 2, channels)
                 assert d["kernel"] == 6 and d["lds_bytes"] <= 64 * 1024 and batch % d["columns_per_lane"] == 0
-                assert d["threads"] in (256, 512) and d["threads"] // 64 <= channels
+                assert d["threads"] in (256, 512) and d["threads"] // 64 <= max(channels, 4)
                 assert d["workgroups"] * d["columns_per_lane"] >= batch
                 patch = (7 * s + k) ** 2 * d["columns_per_lane"] // 4
                 assert patch <= 16 * 64 and d["lds_bytes"] >= d["threads"] // 64 * 16 * patch
