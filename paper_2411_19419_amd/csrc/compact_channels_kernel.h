@@ -5,7 +5,7 @@
 // per channel (each adding to y) is bound by launches and by re-reading y when the planes are
 // small and the channels many.  Here a wave keeps the sums of an 8 x 8 tile of outputs, VB
 // batch columns each, in registers while it walks the channels:
-//   - the W = 4 or 8 waves of a workgroup share the tile and split the channels (wave w
+//   - the W = 4, 8 or 16 waves of a workgroup share the tile and split the channels (wave w
 //     takes channels w, w + W, ...); at the end their partial sums are added in wave order, so
 //     the summation order is fixed;
 //   - per channel a wave copies the (7 s + k)^2 input pixels its tile touches, zero outside
@@ -23,9 +23,11 @@
 namespace convspmv {
 
 constexpr int kChanTile = 8;          // outputs per tile side; 64 lanes = one tile
-constexpr int kChanMinWaves = 4;      // waves per workgroup = ways the channels are split: 4 or 8
-constexpr int kChanMaxWaves = 8;
+constexpr int kChanMinWaves = 4;      // waves per workgroup = ways the channels are split: 4, 8 or 16
 constexpr int kChanItems = 16;        // float4 of a patch per lane, at most (16 KiB of patch per wave)
+// Most waves per workgroup: a lane that carries more than 8 patch items needs more than the 128
+// registers a thread of a 1024-thread workgroup can have.
+constexpr int chan_max_waves(int items_per_lane) { return items_per_lane <= 8 ? 16 : 8; }
 
 struct CompactChannelsGeom {
     int m, n, m_out, n_out, s, p, k;
@@ -55,7 +57,7 @@ __device__ __forceinline__ int2 described_by_position(int m, int n, int k, int s
 // kernel size the tap loops are unrolled for, with the channel's table in scalar registers (0: any
 // k, table in LDS).
 template <int VB, int NI, int KK>
-__global__ __launch_bounds__(kChanMaxWaves *kWave) void spmm_compact_channels_kernel(
+__global__ __launch_bounds__(chan_max_waves(NI) * kWave) void spmm_compact_channels_kernel(
     const int2 *__restrict__ desc, const float *__restrict__ ktab, const float *__restrict__ x, float *__restrict__ y,
     const CompactChannelsGeom g) {
     static_assert(VB == 4 || VB == 8 || VB == 16, "batch columns per lane");

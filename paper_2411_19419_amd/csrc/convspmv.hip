@@ -745,7 +745,7 @@ CompactChoice choose_compact(const conv_plan *plan, const float *x, const float 
 
 // Several channels in one launch (compact_channels_kernel.h): when the channels are many and a
 // channel's product is short, so that one launch per channel would be bound by launches and by
-// re-reading y.  VB batch columns per lane (16, 8 or 4, dividing the batch) and W = 4 or 8
+// re-reading y.  VB batch columns per lane (16, 8 or 4, dividing the batch) and W = 4, 8 or 16
 // waves per workgroup that split the channels: the widest VB whose launch has kChanFusedWaves
 // waves with the most ways that fit LDS and the channel count, else the shape with most waves.
 constexpr double kChanFusedWork = 1e8;        // multiply-adds per channel below which the launches are fused
@@ -776,8 +776,9 @@ ChannelsChoice choose_compact_channels(const conv_plan *plan, const float *x, co
     for (int vb = batch % 16 == 0 ? 16 : (batch % 8 == 0 ? 8 : 4); vb >= 4; vb /= 2) {
         if (ph * ph * (vb / 4) > (int64_t)kChanItems * kWave || batch / vb > 65535) continue;
         const int64_t vec4 = std::max<int64_t>(ph * ph, kWave) * (vb / 4) + ((int64_t)sh.k * sh.k + 3) / 4;
+        const int per_lane = (int)((ph * ph * (vb / 4) + kWave - 1) / kWave);
         int ways = kChanMinWaves;
-        while (ways < kChanMaxWaves && 2 * ways <= plan->channels && vec4 * 16 * 2 * ways <= 64 * 1024) ways *= 2;
+        while (ways < chan_max_waves(per_lane) && 2 * ways <= plan->channels && vec4 * 16 * 2 * ways <= 64 * 1024) ways *= 2;
         if (vec4 * 16 * ways > 64 * 1024) continue;
         const int64_t blocks = tiles_x * tiles_y * (batch / vb);
         while (ways > kChanMinWaves && blocks * (ways / 2) >= kChanFusedWaves) ways /= 2;     // no more ways than the chip needs

@@ -230,8 +230,8 @@ def test_dispatch_of_channel_sums_from_the_structure_aware_storage():
     assert d["kernel"] == 6 and d["threads"] == 256 and d["columns_per_lane"] == 16
     assert d["workgroups"] == 28 * 28 and d["strip"] == d["segment"] == 8
     assert d["lds_bytes"] == 4 * 16 * (10 * 10 * 4 + 3)
-    d = _dispatch(56, 56, 3, 1, 1, 16, 2, 64)                            # 49 tiles: narrow lanes, 8 ways
-    assert d["kernel"] == 6 and d["threads"] == 512 and d["columns_per_lane"] == 4 and d["workgroups"] == 49 * 4
+    d = _dispatch(56, 56, 3, 1, 1, 16, 2, 64)                            # 49 tiles: narrow lanes, 16 ways
+    assert d["kernel"] == 6 and d["threads"] == 1024 and d["columns_per_lane"] == 4 and d["workgroups"] == 49 * 4
     assert _dispatch(224, 224, 3, 1, 1, 32, 2, 64)["workgroups"] == 28 * 28 * 2
     assert _dispatch(224, 224, 3, 1, 1, 8, 2, 64)["columns_per_lane"] == 8
     assert _dispatch(224, 224, 3, 1, 1, 20, 2, 64)["columns_per_lane"] == 4
@@ -247,7 +247,7 @@ def test_dispatch_of_channel_sums_from_the_structure_aware_storage():
             for channels in (4, 12, 100):
                 d = _dispatch(112, 96, k, s, k // 2, batch, 2, channels)
                 assert d["kernel"] == 6 and d["lds_bytes"] <= 64 * 1024 and batch % d["columns_per_lane"] == 0
-                assert d["threads"] in (256, 512) and d["threads"] // 64 <= max(channels, 4)
+                assert d["threads"] in (256, 512, 1024) and d["threads"] // 64 <= max(channels, 4)
                 assert d["workgroups"] * d["columns_per_lane"] >= batch
                 patch = (7 * s + k) ** 2 * d["columns_per_lane"] // 4
                 assert patch <= 16 * 64 and d["lds_bytes"] >= d["threads"] // 64 * 16 * patch
