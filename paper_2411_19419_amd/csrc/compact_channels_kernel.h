@@ -3,12 +3,12 @@
 // A convolution layer adds the products of all its input channels: y = sum_c T_c x_c, every
 // T_c with the row descriptors of Section 2 / Theorem 2.1 and its own k*k table.  One launch
 // per channel (each adding to y) is bound by launches and by re-reading y when the planes are
-// small and the channels many.  Here a wave keeps the sums of an 8 x 8 tile of outputs, VB
+// small and the channels many.  Here a wave keeps the sums of a 4 x 16 tile of outputs, VB
 // batch columns each, in registers while it walks the channels:
 //   - the W = 4, 8 or 16 waves of a workgroup share the tile and split the channels (wave w
 //     takes channels w, w + W, ...); at the end their partial sums are added in wave order, so
 //     the summation order is fixed;
-//   - per channel a wave copies the (7 s + k)^2 input pixels its tile touches, zero outside
+//   - per channel a wave copies the (3 s + k) x (15 s + k) input pixels its tile touches, zero outside
 //     the image, into LDS of its own (no workgroup barrier inside the walk: the LDS
 //     instructions of a wave execute in order), then every lane adds the k x k taps of its
 //     output over that padded patch, while the next channel's pixels are on their way from
@@ -22,7 +22,8 @@
 
 namespace convspmv {
 
-constexpr int kChanTile = 8;          // outputs per tile side; 64 lanes = one tile
+constexpr int kChanTileX = 4;         // output lines and
+constexpr int kChanTileY = 16;        // output columns of a tile; 64 lanes = one tile
 constexpr int kChanMinWaves = 4;      // waves per workgroup = ways the channels are split: 4, 8 or 16
 constexpr int kChanItems = 16;        // float4 of a patch per lane, at most (16 KiB of patch per wave)
 // Most waves per workgroup: a lane that carries more than 8 patch items needs more than the 128
@@ -34,9 +35,9 @@ struct CompactChannelsGeom {
     int batch, channels;
     int tiles_y;          // tiles per line of tiles
     int tiles, tiles_per_xcd;
-    int ph;               // patch side in pixels: 7 s + k
+    int phx, phy;         // patch lines, pixels per patch line: 3 s + k, 15 s + k
     int wave_vec4;        // float4 of LDS per wave: patch (or one partial sum per lane) + the channel's table
-    float inv_ph;
+    float inv_phy;
     long long plane;      // floats per channel of x: m * n * batch
 };
 
@@ -53,7 +54,7 @@ __device__ __forceinline__ int2 described_by_position(int m, int n, int k, int s
     return d;
 }
 
-// VB batch columns per lane; NI float4 of a patch per lane (at least (7 s + k)^2 VB / 256); KK: the
+// VB batch columns per lane; NI float4 of a patch per lane (at least (3 s + k)(15 s + k) VB / 256); KK: the
 // kernel size the tap loops are unrolled for, with the channel's table in scalar registers (0: any
 // k, table in LDS).
 template <int VB, int NI, int KK>
@@ -68,14 +69,14 @@ __global__ __launch_bounds__(chan_max_waves(NI) * kWave) void spmm_compact_chann
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave), lane = tid % kWave;
     const int ways = (int)blockDim.x / kWave;
     float4 *const patch = chan_lds + wave * g.wave_vec4;
-    float *const table = reinterpret_cast<float *>(patch + max(g.ph * g.ph, kWave) * Q);
+    float *const table = reinterpret_cast<float *>(patch + max(g.phx * g.phy, kWave) * Q);
     // consecutive workgroups go to different XCDs; a band of neighbouring tiles to one, so that the pixels
     // two tiles share are fetched into one L2
     const int tile = ((int)blockIdx.x % kXcds) * g.tiles_per_xcd + (int)blockIdx.x / kXcds;
     if ((int)blockIdx.x / kXcds >= g.tiles_per_xcd || tile >= g.tiles) return;      // uniform over the workgroup
     const int tile_x = tile / g.tiles_y, tile_y = tile - tile_x * g.tiles_y;
-    const int lx = lane / kChanTile, ly = lane % kChanTile;
-    const int ox = tile_x * kChanTile + lx, oy = tile_y * kChanTile + ly;
+    const int lx = lane / kChanTileY, ly = lane % kChanTileY;
+    const int ox = tile_x * kChanTileX + lx, oy = tile_y * kChanTileY + ly;
     const bool live = ox < g.m_out && oy < g.n_out;
     const long long row = (long long)ox * g.n_out + oy;
     const int c0 = (int)blockIdx.y * VB;
@@ -96,15 +97,15 @@ __global__ __launch_bounds__(chan_max_waves(NI) * kWave) void spmm_compact_chann
     };
 
     if (as_expected) {
-        const int i_lo = g.s * tile_x * kChanTile - g.p, j_lo = g.s * tile_y * kChanTile - g.p;   // patch origin
-        const int items = g.ph * g.ph * Q;          // float4 of a patch; at most NI * 64
+        const int i_lo = g.s * tile_x * kChanTileX - g.p, j_lo = g.s * tile_y * kChanTileY - g.p;   // patch origin
+        const int items = g.phx * g.phy * Q;         // float4 of a patch; at most NI * 64
         // where this lane's items lie in a channel's plane (floats; -1: outside the image, a zero)
         int at[NI];
 #pragma unroll
         for (int u = 0; u < NI; ++u) {
             const int it = min(u * kWave + lane, items - 1);
             const int pix = it / Q, q = it % Q;
-            const int pi = div_small(pix, g.inv_ph), pj = pix - pi * g.ph;
+            const int pi = div_small(pix, g.inv_phy), pj = pix - pi * g.phy;
             const int i = i_lo + pi, j = j_lo + pj;
             at[u] = i >= 0 && i < g.m && j >= 0 && j < g.n ? (i * g.n + j) * g.batch + 4 * q : -1;
         }
@@ -116,13 +117,18 @@ __global__ __launch_bounds__(chan_max_waves(NI) * kWave) void spmm_compact_chann
             for (int u = 0; u < NI; ++u)
                 if (u * kWave < items) next[u] = *reinterpret_cast<const float4 *>(xc + max(at[u], 0));
         };
-        const float4 *const mine = patch + (lx * g.s * g.ph + ly * g.s) * Q;      // this lane's window in the patch
+        // The patch is kept as Q planes of one float4 per pixel: neighbouring lanes then read neighbouring
+        // 16-byte words (pixel-major with 64 bytes per pixel, 16 lanes met in 4 banks).
+        const int npix = g.phx * g.phy;
+        const float4 *const mine = patch + lx * g.s * g.phy + ly * g.s;     // this lane's window in plane 0
         ask(wave);
         for (int c = wave; c < g.channels; c += ways) {
 #pragma unroll
             for (int u = 0; u < NI; ++u)
-                if (u * kWave < items && u * kWave + lane < items)
-                    patch[u * kWave + lane] = at[u] >= 0 ? next[u] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                if (u * kWave < items && u * kWave + lane < items) {
+                    const int it = u * kWave + lane;
+                    patch[(it % Q) * npix + it / Q] = at[u] >= 0 ? next[u] : make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                }
             if constexpr (KK > 0) {
                 float w[KK * KK];               // the same for every lane: scalar loads, scalar operands
                 const float *tc = ktab + (long long)c * (KK * KK);
@@ -132,11 +138,11 @@ __global__ __launch_bounds__(chan_max_waves(NI) * kWave) void spmm_compact_chann
                 wave_lds_order();
 #pragma unroll
                 for (int a = 0; a < KK; ++a) {
-                    const float4 *line = mine + a * g.ph * Q;
+                    const float4 *line = mine + a * g.phy;
 #pragma unroll
                     for (int b = 0; b < KK; ++b) {
 #pragma unroll
-                        for (int q = 0; q < Q; ++q) fma4(acc[q], w[a * KK + b], line[b * Q + q]);
+                        for (int q = 0; q < Q; ++q) fma4(acc[q], w[a * KK + b], line[q * npix + b]);
                     }
                 }
             } else {
@@ -144,12 +150,12 @@ __global__ __launch_bounds__(chan_max_waves(NI) * kWave) void spmm_compact_chann
                 ask(c + ways);
                 wave_lds_order();
                 for (int a = 0; a < g.k; ++a) {
-                    const float4 *line = mine + a * g.ph * Q;
+                    const float4 *line = mine + a * g.phy;
                     const float *tl = table + a * g.k;
                     for (int b = 0; b < g.k; ++b) {
                         const float w = tl[b];
 #pragma unroll
-                        for (int q = 0; q < Q; ++q) fma4(acc[q], w, line[b * Q + q]);
+                        for (int q = 0; q < Q; ++q) fma4(acc[q], w, line[q * npix + b]);
                     }
                 }
             }

@@ -766,17 +766,18 @@ ChannelsChoice choose_compact_channels(const conv_plan *plan, const float *x, co
     if (((((uintptr_t)x) | ((uintptr_t)y)) & 15u) != 0) return c;
     if ((double)plan->nnz * batch > kChanFusedWork) return c;
     // int arithmetic in the kernel: s*x - p + k over the padded plane, float offsets within a channel's plane
-    if ((int64_t)sh.m + 2LL * sh.p + sh.k + 8LL * sh.s >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + sh.k + 8LL * sh.s >= (1LL << 30) ||
+    if ((int64_t)sh.m + 2LL * sh.p + sh.k + 16LL * sh.s >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + sh.k + 16LL * sh.s >= (1LL << 30) ||
         (int64_t)sh.m * sh.n * batch >= kInt32Limit)
         return c;
-    const int64_t ph = (int64_t)(kChanTile - 1) * sh.s + sh.k;
-    const int64_t tiles_x = (sh.m_out + kChanTile - 1) / kChanTile, tiles_y = (sh.n_out + kChanTile - 1) / kChanTile;
+    const int64_t phx = (int64_t)(kChanTileX - 1) * sh.s + sh.k, phy = (int64_t)(kChanTileY - 1) * sh.s + sh.k;
+    const int64_t npix = phx * phy;
+    const int64_t tiles_x = (sh.m_out + kChanTileX - 1) / kChanTileX, tiles_y = (sh.n_out + kChanTileY - 1) / kChanTileY;
     if (tiles_x * tiles_y + kXcds > kInt32Limit) return c;
     int64_t best_waves = 0;
     for (int vb = batch % 16 == 0 ? 16 : (batch % 8 == 0 ? 8 : 4); vb >= 4; vb /= 2) {
-        if (ph * ph * (vb / 4) > (int64_t)kChanItems * kWave || batch / vb > 65535) continue;
-        const int64_t vec4 = std::max<int64_t>(ph * ph, kWave) * (vb / 4) + ((int64_t)sh.k * sh.k + 3) / 4;
-        const int per_lane = (int)((ph * ph * (vb / 4) + kWave - 1) / kWave);
+        if (npix * (vb / 4) > (int64_t)kChanItems * kWave || batch / vb > 65535) continue;
+        const int64_t vec4 = std::max<int64_t>(npix, kWave) * (vb / 4) + ((int64_t)sh.k * sh.k + 3) / 4;
+        const int per_lane = (int)((npix * (vb / 4) + kWave - 1) / kWave);
         int ways = kChanMinWaves;
         while (ways < chan_max_waves(per_lane) && 2 * ways <= plan->channels && vec4 * 16 * 2 * ways <= 64 * 1024) ways *= 2;
         if (vec4 * 16 * ways > 64 * 1024) continue;
@@ -797,9 +798,10 @@ ChannelsChoice choose_compact_channels(const conv_plan *plan, const float *x, co
         g.m = sh.m; g.n = sh.n; g.m_out = sh.m_out; g.n_out = sh.n_out; g.s = sh.s; g.p = sh.p; g.k = sh.k;
         g.batch = batch; g.channels = plan->channels;
         g.tiles_y = (int)tiles_y;
-        g.ph = (int)ph;
+        g.phx = (int)phx;
+        g.phy = (int)phy;
         g.wave_vec4 = (int)vec4;
-        g.inv_ph = 1.0f / (float)ph;
+        g.inv_phy = 1.0f / (float)phy;
         g.plane = (long long)sh.m * sh.n * batch;
         c.geom = g;
         if (waves >= kChanFusedWaves) break;
@@ -810,7 +812,7 @@ ChannelsChoice choose_compact_channels(const conv_plan *plan, const float *x, co
 template <int VB, int KK>
 void launch_compact_channels_k(const ChannelsChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
     const int threads = c.ways * kWave;
-    const int per_lane = (c.geom.ph * c.geom.ph * (VB / 4) + kWave - 1) / kWave;      // patch items a lane carries
+    const int per_lane = (c.geom.phx * c.geom.phy * (VB / 4) + kWave - 1) / kWave;     // patch items a lane carries
     if (per_lane <= 4)
         spmm_compact_channels_kernel<VB, 4, KK><<<c.grid, threads, c.lds, q>>>(plan->desc, plan->ktab, x, y, c.geom);
     else if (per_lane <= 8)
@@ -1219,7 +1221,8 @@ int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage
         d.kernel = 6;
         d.threads = fused.ways * kWave;
         d.lds_bytes = (int64_t)fused.lds;
-        d.strip = d.segment = kChanTile;
+        d.strip = kChanTileY;
+        d.segment = kChanTileX;
         d.lanes_per_row = 1;
         d.columns_per_lane = fused.vb;
         d.workgroups = (int64_t)fused.geom.tiles * fused.grid.y;
@@ -1270,7 +1273,7 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch) {
     if (plan->compact) {
         const ChannelsChoice fused = choose_compact_channels(plan, nullptr, nullptr, batch);
         if (fused.ok) {
-            snprintf(name, sizeof name, "compact_channels_%dx%d_float4x%d_%d_ways_%d_channels", kChanTile, kChanTile,
+            snprintf(name, sizeof name, "compact_channels_%dx%d_float4x%d_%d_ways_%d_channels", kChanTileX, kChanTileY,
                      fused.vb / 4, fused.ways, plan->channels);
             return name;
         }

@@ -154,13 +154,13 @@ def test_channels_in_one_launch_is_what_runs():
     m, n, k, s, p = 56, 56, 3, 1, 1
     K = torch.zeros(8 * k * k, device=device())
     plan = cs.conv_compact_build(m, n, k, s, p, K, channels=8)
-    # 49 tiles: every batch gets the narrowest lanes (most workgroups) and all eight ways
-    assert plan.variant(16) == "compact_channels_8x8_float4x1_8_ways_8_channels"
-    assert plan.variant(12) == "compact_channels_8x8_float4x1_8_ways_8_channels"
+    # 56 tiles: every batch gets the narrowest lanes (most workgroups) and all eight ways
+    assert plan.variant(16) == "compact_channels_4x16_float4x1_8_ways_8_channels"
+    assert plan.variant(12) == "compact_channels_4x16_float4x1_8_ways_8_channels"
     assert plan.variant(3).startswith("compact_rect")          # batch not a multiple of 4: one launch per channel
     plan.close()
     plan = cs.conv_compact_build(m, n, k, s, p, K[:3 * k * k], channels=3)
-    assert plan.variant(16) == "compact_channels_8x8_float4x1_4_ways_3_channels"      # the fourth wave idles
+    assert plan.variant(16) == "compact_channels_4x16_float4x1_4_ways_3_channels"      # the fourth wave idles
     plan.close()
     plan = cs.conv_compact_build(m, n, k, s, p, K[:k * k])
     assert plan.variant(16).startswith("compact_rect")         # one channel: nothing to sum

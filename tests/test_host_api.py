@@ -224,24 +224,24 @@ def test_dispatch_geometry_is_consistent_over_many_shapes():
 
 def test_dispatch_of_channel_sums_from_the_structure_aware_storage():
     """All channels in one launch when there are several, the batch is a multiple of 4 and a
-    channel's product is short; otherwise the per-channel kernels.  LDS of the four waves' patches
-    of (7 s + k)^2 pixels within 64 KiB, fewer batch columns per lane when they would not fit."""
+    channel's product is short; otherwise the per-channel kernels.  LDS of the waves' patches of
+    (3 s + k) x (15 s + k) pixels within 64 KiB, fewer batch columns per lane when they would not fit."""
     d = _dispatch(224, 224, 3, 1, 1, 16, 2, 64)                          # 784 tiles: full lines per lane, 4 ways
     assert d["kernel"] == 6 and d["threads"] == 256 and d["columns_per_lane"] == 16
-    assert d["workgroups"] == 28 * 28 and d["strip"] == d["segment"] == 8
-    assert d["lds_bytes"] == 4 * 16 * (10 * 10 * 4 + 3)
-    d = _dispatch(56, 56, 3, 1, 1, 16, 2, 64)                            # 49 tiles: narrow lanes, 16 ways
-    assert d["kernel"] == 6 and d["threads"] == 1024 and d["columns_per_lane"] == 4 and d["workgroups"] == 49 * 4
-    assert _dispatch(224, 224, 3, 1, 1, 32, 2, 64)["workgroups"] == 28 * 28 * 2
+    assert d["workgroups"] == 56 * 14 and d["strip"] == 16 and d["segment"] == 4
+    assert d["lds_bytes"] == 4 * 16 * (6 * 18 * 4 + 3)
+    d = _dispatch(56, 56, 3, 1, 1, 16, 2, 64)                            # 56 tiles: narrow lanes, 16 ways
+    assert d["kernel"] == 6 and d["threads"] == 1024 and d["columns_per_lane"] == 4 and d["workgroups"] == 14 * 4 * 4
+    assert _dispatch(224, 224, 3, 1, 1, 32, 2, 64)["workgroups"] == 56 * 14 * 2
     assert _dispatch(224, 224, 3, 1, 1, 8, 2, 64)["columns_per_lane"] == 8
     assert _dispatch(224, 224, 3, 1, 1, 20, 2, 64)["columns_per_lane"] == 4
     assert _dispatch(56, 56, 3, 1, 1, 6, 2, 64)["kernel"] == 5          # batch not a multiple of 4
     assert _dispatch(56, 56, 3, 1, 1, 16, 2, 3)["threads"] == 256       # fewer channels than waves: the fourth idles
     assert _dispatch(56, 56, 3, 1, 1, 16, 2, 1)["kernel"] == 5          # one channel: nothing to sum
     assert _dispatch(1024, 1024, 7, 1, 3, 16, 2, 64)["kernel"] == 5     # long products
-    d = _dispatch(150, 150, 13, 1, 6, 16, 2, 8)                          # 20 x 20 patch: 16 columns per lane do not fit
+    d = _dispatch(150, 150, 13, 1, 6, 16, 2, 8)                          # 16 x 28 patch: 16 columns per lane do not fit
     assert d["kernel"] == 6 and d["columns_per_lane"] == 8 and d["lds_bytes"] <= 64 * 1024
-    assert _dispatch(100, 100, 40, 1, 20, 16, 2, 8)["kernel"] == 4      # 47 x 47 patch: no fit, described rows
+    assert _dispatch(100, 100, 40, 1, 20, 16, 2, 8)["kernel"] == 4      # 43 x 55 patch: no fit, described rows
     for k, s in ((1, 1), (3, 1), (3, 2), (5, 1), (7, 2), (9, 3), (11, 1)):
         for batch in (4, 8, 12, 16, 64):
             for channels in (4, 12, 100):
@@ -249,7 +249,7 @@ def test_dispatch_of_channel_sums_from_the_structure_aware_storage():
                 assert d["kernel"] == 6 and d["lds_bytes"] <= 64 * 1024 and batch % d["columns_per_lane"] == 0
                 assert d["threads"] in (256, 512, 1024) and d["threads"] // 64 <= max(channels, 4)
                 assert d["workgroups"] * d["columns_per_lane"] >= batch
-                patch = (7 * s + k) ** 2 * d["columns_per_lane"] // 4
+                patch = (3 * s + k) * (15 * s + k) * d["columns_per_lane"] // 4
                 assert patch <= 16 * 64 and d["lds_bytes"] >= d["threads"] // 64 * 16 * patch
 
 
