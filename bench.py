@@ -427,6 +427,26 @@ def main():
                 avg = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
                 side["product_from_csc"] = {"ms_avg": avg, "useful_tflops": 2.0 * pl.nnz * w.batch / (avg * 1e-3) / 1e12}
             pl.close()
+        # a layer-like sum over input channels (56 x 56, k = 3, 64 channels, this batch) from both storages
+        cm, cn, ck, cs_, cp, cc = 56, 56, 3, 1, 1, 64
+        Kc = torch.empty(cc * ck * ck, dtype=torch.float32, device=dev).normal_()
+        xc = torch.empty(cc * cm * cn * w.batch, dtype=torch.float32, device=dev).normal_()
+        for tag, pl in (("channel_sum_csr", cs.conv_csr_build_channels(cm, cn, ck, cs_, cp, Kc, cc)),
+                        ("channel_sum_compact", cs.conv_compact_build(cm, cn, ck, cs_, cp, Kc, channels=cc))):
+            yc = torch.empty(pl.rows * w.batch, dtype=torch.float32, device=dev)
+            for _ in range(20):
+                cs.conv_spmv(pl, xc, yc, batch=w.batch)
+            torch.cuda.synchronize()
+            pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
+            for a, b in pairs:
+                a.record(stream)
+                cs.conv_spmv(pl, xc, yc, batch=w.batch)
+                b.record(stream)
+            torch.cuda.synchronize()
+            avg = sum(a.elapsed_time(b) for a, b in pairs) / len(pairs)
+            side[tag] = {"shape": [cm, cn, ck, cs_, cp], "channels": cc, "kernel": pl.variant(w.batch), "ms_avg": avg,
+                         "useful_tflops": 2.0 * pl.nnz * cc * w.batch / (avg * 1e-3) / 1e12}
+            pl.close()
         out["side_paths"] = side
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, x_h, K_h, args.transposed)
