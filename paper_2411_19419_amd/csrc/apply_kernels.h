@@ -127,7 +127,14 @@ __global__ __launch_bounds__(kGatherThreads) void spmm_gather_vec_kernel(
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(kGatherThreads) void fill_zero_kernel(float *__restrict__ y, long long count) {
     const long long stride = (long long)gridDim.x * kGatherThreads;
-    for (long long i = (long long)blockIdx.x * kGatherThreads + threadIdx.x; i < count; i += stride) y[i] = 0.0f;
+    const long long first = (long long)blockIdx.x * kGatherThreads + threadIdx.x;
+    // 16-byte stores over the aligned middle, single floats before and after it
+    const long long head = min(count, (long long)((16 - (reinterpret_cast<uintptr_t>(y) & 15u)) & 15u) / 4);
+    const long long quads = (count - head) / 4;
+    float4 *const mid = reinterpret_cast<float4 *>(y + head);
+    for (long long i = first; i < quads; i += stride) mid[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    for (long long i = first; i < head; i += stride) y[i] = 0.0f;
+    for (long long i = head + 4 * quads + first; i < count; i += stride) y[i] = 0.0f;
 }
 
 // BL consecutive lanes take BL neighbouring batch columns of one entry, so that their adds fall

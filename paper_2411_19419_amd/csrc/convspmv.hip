@@ -1048,7 +1048,7 @@ int conv_spmv_from_csc(const conv_plan *plan, const float *x_dev, float *y_dev, 
     }
     hipStream_t q = (hipStream_t)stream;
     const long long count = (long long)out_pixels * batch;
-    const unsigned fill_blocks = (unsigned)std::min<long long>((count + kGatherThreads - 1) / kGatherThreads, 1 << 16);
+    const unsigned fill_blocks = (unsigned)std::min<long long>((count / 4 + kGatherThreads) / kGatherThreads, 1 << 16);
     fill_zero_kernel<<<fill_blocks, kGatherThreads, 0, q>>>(y_dev, count);
     CscTileChoice tc{};
     if (plan->nnz > 0) tc = choose_csc_tile(plan, batch);

@@ -225,6 +225,28 @@ def test_product_from_the_csc_arrays_is_the_convolution(shape, batch):
     plan.close()
 
 
+@pytest.mark.parametrize("offset,batch", [(1, 1), (3, 2), (2, 5), (1, 16)])
+def test_product_from_csc_into_an_unaligned_result(offset, batch):
+    """y that does not start on a 16-byte boundary (the zero fill before the scatter uses 16-byte
+    stores over the aligned middle); the floats around y stay untouched."""
+    shape = (45, 38, 5, 1, 2)
+    m, n, k, s, p = shape
+    rng = np.random.default_rng(31)
+    x = rng.standard_normal(m * n * batch).astype(np.float32)
+    K = rng.standard_normal(k * k).astype(np.float32)
+    plan = build_plan_t(shape, K)
+    count = plan.cols * batch
+    buf = torch.full((count + 8,), 7.0, dtype=torch.float32, device=device())
+    cs.conv_spmv_from_csc(plan, torch.from_numpy(x).to(device()), buf[offset:offset + count], batch=batch)
+    torch.cuda.synchronize()
+    got = buf.cpu().numpy()
+    assert np.all(got[:offset] == 7.0) and np.all(got[offset + count:] == 7.0)
+    ref, scale = oracle.conv(m, n, k, s, p, x, K, batch=batch, want_scale=True)
+    err = np.abs(got[offset:offset + count].astype(np.float64) - ref.astype(np.float64))
+    assert np.all(err <= 1e-5 * scale + 1e-30)
+    plan.close()
+
+
 def test_product_from_csc_reads_the_stored_arrays():
     """The scatter uses the stored row indices and values, wherever they point: one entry of a
     column is sent to a row far from the pixel's windows (outside what the workgroup keeps on
