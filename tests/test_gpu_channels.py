@@ -121,6 +121,10 @@ def test_channel_errors():
     ((56, 56, 3, 1, 1), 64, 16), ((61, 43, 3, 1, 1), 5, 16), ((61, 43, 5, 2, 2), 7, 8), ((37, 53, 7, 1, 3), 4, 32),
     ((28, 28, 1, 1, 0), 9, 16), ((40, 45, 7, 2, 3), 6, 16), ((30, 30, 13, 1, 6), 4, 16), ((7, 7, 3, 1, 1), 33, 4),
     ((20, 22, 3, 1, 12), 4, 16), ((33, 31, 4, 3, 5), 5, 12), ((112, 112, 3, 2, 1), 16, 16),
+    # planes with enough tiles for 16 and 8 batch columns per lane; patches of 5 to 16 items per lane;
+    # unrolled (k = 3, 7) and looped (k = 5) taps at those widths
+    ((224, 224, 3, 1, 1), 64, 16), ((224, 224, 3, 1, 1), 6, 8), ((300, 300, 7, 1, 3), 5, 16),
+    ((256, 256, 5, 1, 2), 6, 16), ((448, 448, 7, 2, 3), 4, 8),
 ])
 def test_channel_sum_from_the_structure_aware_storage(shape, channels, batch):
     m, n, k, s, p = shape
@@ -159,6 +163,11 @@ def test_channels_in_one_launch_is_what_runs():
     assert plan.variant(12) == "compact_channels_4x16_float4x1_8_ways_8_channels"
     assert plan.variant(3).startswith("compact_rect")          # batch not a multiple of 4: one launch per channel
     plan.close()
+    for shape, channels, batch, want in [((224, 224, 3, 1, 1), 64, 16, "float4x4_4_ways"), ((224, 224, 3, 1, 1), 6, 8, "float4x2_4_ways"),
+                                         ((300, 300, 7, 1, 3), 5, 16, "float4x4_4_ways"), ((448, 448, 7, 2, 3), 4, 8, "float4x2_4_ways")]:
+        big = cs.conv_compact_build(*shape, torch.zeros(channels * shape[2] ** 2, device=device()), channels=channels)
+        assert big.variant(batch) == "compact_channels_4x16_%s_%d_channels" % (want, channels)
+        big.close()
     plan = cs.conv_compact_build(m, n, k, s, p, K[:3 * k * k], channels=3)
     assert plan.variant(16) == "compact_channels_4x16_float4x1_4_ways_3_channels"      # the fourth wave idles
     plan.close()

@@ -78,6 +78,31 @@ def test_transposed_named_workloads_full_size(name):
     plan.close()
 
 
+@pytest.mark.parametrize("name", ["strided_256_k5_b64", "headline_1024_k7_b1", "headline_1024_k7_b16",
+                                  "padheavy_512_k9_s3", "cnn_224_k3_b256"])
+def test_product_from_csc_named_workloads_full_size(name):
+    """y = T x from the column-compressed arrays at the sizes the benchmark times, the whole result
+    against the sliding-window oracle."""
+    w = workloads.WORKLOADS[name]
+    batch = min(w.batch, 64)
+    m, n, k, s, p = w.shape
+    rng = np.random.default_rng(17)
+    x = rng.standard_normal(m * n * batch).astype(np.float32)
+    K = rng.standard_normal(k * k).astype(np.float32)
+    plan = build_plan_t(w.shape, K)
+    y = cs.conv_spmv_from_csc(plan, torch.from_numpy(x).to(device()), batch=batch)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    ref, scale = oracle.conv(m, n, k, s, p, x, K, batch=batch, want_scale=True)
+    live = scale > 0
+    assert np.all(got[~live] == 0.0)
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    worst = float(np.max(err[live] / scale[live]))
+    print("%s from CSC: max err/scale %.2e" % (name, worst))
+    assert worst <= 1e-5
+    plan.close()
+
+
 def test_adjoint_identity_on_the_device():
     """<T x, u> = <x, T^T u> with both products from the GPU (integers: exact in fp32)."""
     shape, batch = (60, 44, 5, 2, 2), 1
