@@ -498,3 +498,48 @@ def test_graph_replays_match_eager_applies():
             assert torch.equal(y, e), (rep, pl.variant(batch))
     for pl in plans:
         pl.close()
+
+
+def test_graph_replays_of_channel_sums_and_of_the_csc_product():
+    """The same for the sums over channels (one launch from the structure-aware storage, the
+    row-group kernel and the per-channel launches from CSR: bit for bit) and for y = T x from the
+    column-compressed arrays (a fill kernel and a scatter; its adds arrive in timing order, so
+    replays are compared with the eager result to the parity tolerance)."""
+    shape, channels, batch = (120, 136, 3, 1, 1), 6, 16
+    m, n, k, s, p = shape
+    rng = np.random.default_rng(43)
+    Kd = torch.from_numpy(rng.standard_normal(channels * k * k).astype(np.float32)).to(device())
+    sums = [cs.conv_compact_build(m, n, k, s, p, Kd, channels=channels), cs.conv_csr_build_channels(m, n, k, s, p, Kd, channels)]
+    assert sums[0].variant(batch).startswith("compact_channels")
+    tshape = (300, 520, 7, 1, 3)
+    Kt = rng.standard_normal(49).astype(np.float32)
+    csc = cs.conv_csc_build(*tshape, torch.from_numpy(Kt).to(device()))
+    xs = [torch.empty(pl.cols * batch, dtype=torch.float32, device=device()).normal_() for pl in sums]
+    ys = [torch.empty(pl.rows * batch, dtype=torch.float32, device=device()) for pl in sums]
+    xt = torch.empty(csc.rows * batch, dtype=torch.float32, device=device()).normal_()
+    yt = torch.empty(csc.cols * batch, dtype=torch.float32, device=device())
+    for pl, x, y in zip(sums, xs, ys):           # first launches outside the capture
+        cs.conv_spmv(pl, x, y, batch=batch)
+    cs.conv_spmv_from_csc(csc, xt, yt, batch=batch)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for pl, x, y in zip(sums, xs, ys):
+            cs.conv_spmv(pl, x, y, batch=batch)
+        cs.conv_spmv_from_csc(csc, xt, yt, batch=batch)
+    for rep in range(4):
+        for x in xs + [xt]:
+            x.normal_()
+        eager = [cs.conv_spmv(pl, x, batch=batch) for pl, x in zip(sums, xs)]
+        torch.cuda.synchronize()
+        for y in ys + [yt]:
+            y.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        for pl, y, e in zip(sums, ys, eager):
+            assert torch.equal(y, e), (rep, pl.variant(batch))
+        ref, scale = oracle.conv(*tshape, xt.cpu().numpy(), Kt, batch=batch, want_scale=True)
+        err = np.abs(yt.cpu().numpy().astype(np.float64) - ref.astype(np.float64))
+        assert np.all(err <= REL_TOL * scale + 1e-30), rep
+    for pl in sums + [csc]:
+        pl.close()
