@@ -154,6 +154,33 @@ def test_channel_sum_from_the_structure_aware_storage(shape, channels, batch):
     plan.close()
 
 
+def test_channel_sums_in_one_launch_on_random_small_shapes():
+    """Two hundred random shapes (planes up to 60 x 60, k up to 9, strides up to 4, paddings up to
+    8) with 2 to 9 channels at batches 4, 8, 12 and 16: ragged tiles on both sides, tiles wholly in
+    the padding, channel counts that leave waves without work."""
+    rng = np.random.default_rng(2025)
+    done = fused = 0
+    while done < 200:
+        k, s, p = int(rng.integers(1, 10)), int(rng.integers(1, 5)), int(rng.integers(0, 9))
+        m, n = (int(v) for v in rng.integers(1, 61, size=2))
+        if k > m + 2 * p or k > n + 2 * p:
+            continue
+        channels, batch = int(rng.integers(2, 10)), (4, 8, 12, 16)[done % 4]
+        x, K = _case((m, n, k, s, p), channels, batch, 1000 + done)
+        plan = cs.conv_compact_build(m, n, k, s, p, torch.from_numpy(K).to(device()), channels=channels)
+        fused += plan.variant(batch).startswith("compact_channels")       # not when (3 s + k)(15 s + k) pixels do not fit
+        y = cs.conv_spmv(plan, torch.from_numpy(x).to(device()), batch=batch)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        ref, scale = oracle.conv_channels(m, n, k, s, p, x, K, channels, batch=batch, want_scale=True)
+        err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+        assert np.all(got[scale == 0] == 0.0), (m, n, k, s, p, channels, batch)
+        assert np.all(err <= REL_TOL * scale), (m, n, k, s, p, channels, batch)
+        plan.close()
+        done += 1
+    assert fused >= 150, fused
+
+
 def test_channels_in_one_launch_is_what_runs():
     m, n, k, s, p = 56, 56, 3, 1, 1
     K = torch.zeros(8 * k * k, device=device())

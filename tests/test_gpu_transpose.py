@@ -250,6 +250,33 @@ def test_product_from_the_csc_arrays_is_the_convolution(shape, batch):
     plan.close()
 
 
+def test_product_from_csc_on_random_small_shapes():
+    """Three hundred random shapes (planes up to 70 x 70, k up to 12, strides up to 5, paddings up
+    to 9: windows clipped on every side, pixels no window covers, tiles of one line or one
+    column) at the batch widths that select every lane layout of the scatter."""
+    rng = np.random.default_rng(2024)
+    batches = [1, 2, 3, 4, 5, 8, 9, 16, 20]
+    done = 0
+    while done < 300:
+        k, s, p = int(rng.integers(1, 13)), int(rng.integers(1, 6)), int(rng.integers(0, 10))
+        m, n = (int(v) for v in rng.integers(1, 71, size=2))
+        if k > m + 2 * p or k > n + 2 * p:
+            continue
+        batch = batches[done % len(batches)]
+        x = rng.standard_normal(m * n * batch).astype(np.float32)
+        K = rng.standard_normal(k * k).astype(np.float32)
+        plan = build_plan_t((m, n, k, s, p), K)
+        y = cs.conv_spmv_from_csc(plan, torch.from_numpy(x).to(device()), batch=batch)
+        torch.cuda.synchronize()
+        got = y.cpu().numpy()
+        ref, scale = oracle.conv(m, n, k, s, p, x, K, batch=batch, want_scale=True)
+        err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+        assert np.all(got[scale == 0] == 0.0), (m, n, k, s, p, batch)
+        assert np.all(err <= 1e-5 * scale), (m, n, k, s, p, batch)
+        plan.close()
+        done += 1
+
+
 @pytest.mark.parametrize("offset,batch", [(1, 1), (3, 2), (2, 5), (1, 16)])
 def test_product_from_csc_into_an_unaligned_result(offset, batch):
     """y that does not start on a 16-byte boundary (the zero fill before the scatter uses 16-byte
