@@ -214,7 +214,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--streams", type=int, default=2, help="HIP streams the timed applies alternate on")
+    ap.add_argument("--streams", type=int, default=3, help="HIP streams the timed applies take turns on")
     ap.add_argument("--workload", default=None,
                     help="name in workloads.WORKLOADS (default: the headline), or densenet121_sweep")
     ap.add_argument("--batch", type=int, default=1, help="batch of the densenet121_sweep workload")
@@ -284,10 +284,11 @@ def main():
     y = torch.empty(plan.rows * w.batch, dtype=torch.float32, device=dev)
 
     # ---- warm-up, then exactly K steps between two synchronisations.  The K applies are
-    # independent of each other (a stream of batches through one T), so they are issued
-    # alternately on two HIP streams, each with its own output buffer: the start of one
-    # apply then overlaps the tail of the previous one.  The same K applies issued on a
-    # single stream are timed as well and reported as ms_per_step_one_stream.
+    # independent of each other (a stream of batches through one T), so they are issued in
+    # turn on three HIP streams, each with its own output buffer: the start of one apply then
+    # overlaps the tails of the ones before it (three measured better than two or four: 92,
+    # 99.5 and 97 us per apply).  The same K applies issued on a single stream are timed as
+    # well and reported as ms_per_step_one_stream.
     n_streams = max(1, args.streams)
     side = [torch.cuda.Stream() for _ in range(n_streams)] if n_streams > 1 else [stream]
     ys = [y] + [torch.empty_like(y) for _ in range(n_streams - 1)]
