@@ -51,6 +51,7 @@ struct MarchGeom {
     int iw_pitch;         // LDS pixels per ring line (>= iw)
     float inv_n;          // 1.0f / n
     int accum;            // 1: add to y instead of storing (later channels of a multi-channel sum)
+    int col_blocks;       // blocks of batch columns (4*NV each, or 1): batch / (4*NV), or batch
 };
 
 // NV: float4 column chunks per lane (NV planes in LDS, 4*NV batch columns per
@@ -82,14 +83,17 @@ __global__ __launch_bounds__(512, 4) void spmm_march_kernel(const int *__restric
     extern __shared__ float4 smem[];
     elem_t *xs = reinterpret_cast<elem_t *>(smem);   // [NP planes][CS pixels]; pixel (line i, column j) at (i % NL)*pitch + (j - j0)
 
-    // ---- which strip segment (XCD-aware: an XCD owns a band of output lines across all strips)
-    const int local = blockIdx.x / kXcds;
+    // ---- which strip segment (XCD-aware: an XCD owns a band of output lines across all strips) and
+    // which block of batch columns.  The column blocks of one segment are consecutive workgroups of
+    // one XCD: they read the same entries at about the same time, so all but one find them in its L2.
+    const int turn = blockIdx.x / kXcds;
+    const int local = turn / g.col_blocks, col_block = turn - local * g.col_blocks;
     const int job = (blockIdx.x % kXcds) * g.blocks_per_xcd + local;
     if (local >= g.blocks_per_xcd || job >= g.strips * g.segs) return;      // uniform over the block
     const int sg = job / g.strips, tx = job - sg * g.strips;
     const int y0 = tx * TW, xa = sg * g.seg, xb = min(xa + g.seg, g.m_out);
     const int twc = min(TW, g.n_out - y0);
-    const int c0 = blockIdx.y * NVAL;
+    const int c0 = col_block * NVAL;
     const int tid = threadIdx.x, lane = tid % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int gl = lane % G, gr = lane / G;

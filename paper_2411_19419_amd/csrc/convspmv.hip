@@ -605,8 +605,11 @@ bool launch_march_inst(const ApplyChoice &c, const conv_plan *plan, const float 
     auto kern = spmm_march_kernel<G, NIT, NV, TW, NL, LS, XLD, march_plane(NV)>;
     static thread_local bool allowed[64];
     if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
-    const dim3 grid((unsigned)(c.march.blocks_per_xcd * kXcds), (unsigned)(NV ? c.march.batch / (4 * NV) : c.march.batch));
-    kern<<<grid, c.threads, c.lds, q>>>(plan->row_ptr, plan->col_idx, plan->vals, x, y, c.march);
+    MarchGeom g = c.march;
+    g.col_blocks = NV ? g.batch / (4 * NV) : g.batch;
+    const int64_t blocks = (int64_t)g.blocks_per_xcd * kXcds * g.col_blocks;
+    if (blocks > kInt32Limit) return false;
+    kern<<<dim3((unsigned)blocks), c.threads, c.lds, q>>>(plan->row_ptr, plan->col_idx, plan->vals, x, y, g);
     return true;
 }
 
