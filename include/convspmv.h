@@ -183,8 +183,8 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
  * elements, y_dev m_out*n_out*batch, both batch-minor.  By columns the product
  * is a scatter: y is zeroed, then every stored entry adds vals[e]*x[column] to
  * y[row_idx[e]].  The sums of a tile of neighbouring pixels are collected on
- * chip and added to y with hardware float adds (for 3 <= ceil(k/s) <= 32;
- * otherwise every entry is added to y directly).  The result is that of
+ * chip and added to y with hardware float adds (for 2 <= ceil(k/s) <= 32, from
+ * 3 at batches below 4; otherwise every entry is added to y directly).  The result is that of
  * conv_spmv on the CSR plan of the same T up to the order of the additions,
  * which here depends on timing: repeated calls agree to rounding, not bit for
  * bit.  The arrays are read as stored: every row_idx must be in

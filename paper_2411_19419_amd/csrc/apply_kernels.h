@@ -165,9 +165,11 @@ __global__ __launch_bounds__(kGatherThreads) void spmm_scatter_kernel(
 // instruction against 8 for a read, an add and a write), so the sums are plain
 // read-add-write and the lanes are laid out so that no two of them ever meet in one slot:
 //  * each wave owns VB batch columns and a window image of its own, so waves never share;
-//  * the 64 lanes of one step are consecutive entries of ONE column (each lane adds its
-//    entry's VB products), and the entries of a column have pairwise different rows (the
-//    arrays come from conv_csc_build, which writes every (row, column) pair once);
+//  * the lanes of one step are entries of ONE column (each lane adds its entry's VB
+//    products), and the entries of a column have pairwise different rows (the arrays come
+//    from conv_csc_build, which writes every (row, column) pair once) -- or, where columns
+//    are short, of several columns k pixels apart, each entry admitted only to the places
+//    its own pixel's windows can have, which differ from pixel to pixel at that distance;
 //  * a wave's LDS instructions execute in order, so the writes of one step are seen by the
 //    reads of the next.
 // The entries of one tile line are contiguous in the arrays; the workgroup copies them into
@@ -184,6 +186,8 @@ struct CscTileGeom {
     int limit;                     // (wx - 1) * n_out + wy, at most 2^21: rows base .. base + limit - 1 can be in the window
     int stage;                     // entries per stage buffer, tj * (most entries of a column) <= kCscStage
     int ptrs;                      // ints set aside for the column pointers, ti * (tj + 1) rounded up to 4
+    int column_max;                // most entries of a column: ceil(k/s)^2
+    int group, spacing;            // columns per step (64 / column_max, at least 1) and their distance, k pixels
     float inv_wy, inv_n_out;
 };
 
@@ -213,6 +217,11 @@ __global__ __launch_bounds__(W *kWave) void spmm_csc_tile_kernel(
     const int lines = min(g.ti, g.m - i0), ncols = min(g.tj, g.n - j0);
     const long long tile_col0 = (long long)i0 * g.n + j0;
     const int skip = g.n_out - g.wy;             // rows between the end of one run and the start of the next
+    // several columns per step: this lane's column among them and its entry in that column; the places in
+    // a run that the windows over column `lane` of the tile can have (lane l holds column l's)
+    const int lane_group = lane / g.column_max, lane_entry = lane - lane_group * g.column_max;
+    const int reach_col = j0 + min(lane, ncols - 1), y_lo = first_window(j0, g.k, g.s, g.p);
+    const int reach_lo = first_window(reach_col, g.k, g.s, g.p) - y_lo, reach_hi = (reach_col + g.p) / g.s - y_lo;
 
     for (int t = tid; t < lines * (g.tj + 1); t += NT) {
         const int li = t / (g.tj + 1), cj = t - li * (g.tj + 1);
@@ -228,7 +237,7 @@ __global__ __launch_bounds__(W *kWave) void spmm_csc_tile_kernel(
             const int rp = row - base;
             const bool near = (unsigned)rp < (unsigned)g.limit;
             const int lx = div_small(near ? rp : 0, g.inv_n_out), ly = rp - lx * g.n_out;
-            int slot = rp - lx * skip;
+            int slot = (rp - lx * skip) | ly << 16;       // the slot, and above it the row's place in its run
             if (!near || ly >= g.wy) {
                 slot = -1;
                 const int *lp = ptrs + li * (g.tj + 1);
@@ -285,45 +294,82 @@ __global__ __launch_bounds__(W *kWave) void spmm_csc_tile_kernel(
             const int line_beg = __builtin_amdgcn_readfirstlane(cp);
             // entries e .. of a column that ends at `end`, one per lane, from the stage
             auto fetch = [&](int e, int end) { return cur[max(min(min(e, end - 1) - line_beg, g.stage - 1), 0)]; };
-            int end = line_beg;
-            int2 ahead = fetch(line_beg + lane, __builtin_amdgcn_readlane(cp, 1));
-            for (int t = 0; t < ncols; ++t) {
-                const int beg = end;
-                end = __builtin_amdgcn_readlane(cp, t + 1);
-                int2 ev = ahead;
-                // the first 64 entries of the next column are fetched before this column's sums
-                if (t + 1 < ncols) ahead = fetch(end + lane, __builtin_amdgcn_readlane(cp, t + 2));
-                if (beg >= end) continue;
-                float xq[VB];
+            // this lane's entry into its slot of the wave's window
+            auto add = [&](int slot_at, float val, const float (&xq)[VB]) {
+                if (VB % 4 == 0) {
+                    // planes of four batch columns: neighbouring slots are 16 bytes apart in each
+                    float4 *const slot = reinterpret_cast<float4 *>(mine) + slot_at;
+                    float4 q[VB / 4 + 1];
 #pragma unroll
-                for (int v = 0; v < VB; ++v)
-                    xq[v] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(xl[v]), t));
-                for (int e0 = beg; e0 < end; e0 += kWave) {      // entries e0 .. e0 + 63 of column t
-                    if (e0 > beg) ev = fetch(e0 + lane, end);
-                    const float val = __int_as_float(ev.y);
-                    if (e0 + lane < end && ev.x >= 0) {
-                        if (VB % 4 == 0) {
-                            // planes of four batch columns: neighbouring slots are 16 bytes apart in each
-                            float4 *const slot = reinterpret_cast<float4 *>(mine) + ev.x;
-                            float4 q[VB / 4 + 1];
+                    for (int v = 0; v < VB / 4; ++v) q[v] = slot[v * slots];
 #pragma unroll
-                            for (int v = 0; v < VB / 4; ++v) q[v] = slot[v * slots];
+                    for (int v = 0; v < VB / 4; ++v) {
+                        q[v].x = fmaf(val, xq[4 * v], q[v].x);
+                        q[v].y = fmaf(val, xq[4 * v + 1], q[v].y);
+                        q[v].z = fmaf(val, xq[4 * v + 2], q[v].z);
+                        q[v].w = fmaf(val, xq[4 * v + 3], q[v].w);
+                    }
 #pragma unroll
-                            for (int v = 0; v < VB / 4; ++v) {
-                                q[v].x = fmaf(val, xq[4 * v], q[v].x);
-                                q[v].y = fmaf(val, xq[4 * v + 1], q[v].y);
-                                q[v].z = fmaf(val, xq[4 * v + 2], q[v].z);
-                                q[v].w = fmaf(val, xq[4 * v + 3], q[v].w);
+                    for (int v = 0; v < VB / 4; ++v) slot[v * slots] = q[v];
+                } else {
+                    float *const slot = mine + slot_at * VB;
+#pragma unroll
+                    for (int v = 0; v < VB; ++v) slot[v] = fmaf(val, xq[v], slot[v]);
+                }
+            };
+            if (g.group > 1) {
+                // Short columns: a step takes up to g.group columns that lie g.spacing = k pixels apart.  No
+                // window covers two such pixels (Section 2: window y covers pixels s y - p .. s y - p + k - 1),
+                // so their rows lie in different places of a run; an entry is added in LDS only if its place is
+                // one its pixel's windows can have (checked on the stored row), anything else goes to y directly.
+                for (int first = 0; first < g.spacing; ++first)
+                    for (int c_first = first; c_first < ncols; c_first += g.group * g.spacing) {
+                        const int mine_col = c_first + lane_group * g.spacing;
+                        const bool has = lane_group < g.group && mine_col < ncols;
+                        const int cl = has ? mine_col : 0;
+                        int e = __shfl(cp, cl) + lane_entry;
+                        const int end = __shfl(cp, cl + 1);
+                        const int lo = __shfl(reach_lo, cl), hi = __shfl(reach_hi, cl);
+                        float xq[VB];
+#pragma unroll
+                        for (int v = 0; v < VB; ++v) xq[v] = __shfl(xl[v], cl);
+                        while (__builtin_amdgcn_ballot_w64(has && e < end) != 0) {
+                            const int2 ev = fetch(e, end);
+                            const float val = __int_as_float(ev.y);
+                            if (has && e < end && ev.x >= 0) {
+                                const int slot_at = ev.x & 0xffff, place = ev.x >> 16;
+                                if (place >= lo && place <= hi) {
+                                    add(slot_at, val, xq);
+                                } else {
+                                    const long long row = (long long)base + slot_at + (long long)div_small(slot_at, g.inv_wy) * skip;
+#pragma unroll
+                                    for (int v = 0; v < VB; ++v)
+                                        if (cw + v < g.batch) unsafeAtomicAdd(y + row * g.batch + cw + v, val * xq[v]);
+                                }
                             }
-#pragma unroll
-                            for (int v = 0; v < VB / 4; ++v) slot[v * slots] = q[v];
-                        } else {
-                            float *const slot = mine + ev.x * VB;
-#pragma unroll
-                            for (int v = 0; v < VB; ++v) slot[v] = fmaf(val, xq[v], slot[v]);
+                            wave_lds_order();
+                            e += g.column_max;
                         }
                     }
-                    wave_lds_order();
+            } else {
+                int end = line_beg;
+                int2 ahead = fetch(line_beg + lane, __builtin_amdgcn_readlane(cp, 1));
+                for (int t = 0; t < ncols; ++t) {
+                    const int beg = end;
+                    end = __builtin_amdgcn_readlane(cp, t + 1);
+                    int2 ev = ahead;
+                    // the first 64 entries of the next column are fetched before this column's sums
+                    if (t + 1 < ncols) ahead = fetch(end + lane, __builtin_amdgcn_readlane(cp, t + 2));
+                    if (beg >= end) continue;
+                    float xq[VB];
+#pragma unroll
+                    for (int v = 0; v < VB; ++v)
+                        xq[v] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(xl[v]), t));
+                    for (int e0 = beg; e0 < end; e0 += kWave) {      // entries e0 .. e0 + 63 of column t
+                        if (e0 > beg) ev = fetch(e0 + lane, end);
+                        if (e0 + lane < end && ev.x >= 0) add(ev.x & 0xffff, __int_as_float(ev.y), xq);
+                        wave_lds_order();
+                    }
                 }
             }
             if (li + 1 < lines) {

@@ -963,11 +963,14 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
 // of instructions it issues and needs many resident waves, so small LDS footprints are tried
 // first: among the tiles within a footprint the one with the smallest window per pixel wins; a
 // launch too small to fill the chip is charged for the idle units.  Not ok when no tile fits
-// (k above about 32 s) or when the columns are so short (k < 3 s) that a step, which takes the
-// entries of one column, would leave most lanes idle: then every entry is added to y directly.
+// (k above about 32 s) or when the columns are very short (k <= s, or k <= 2 s at batches below 4):
+// the walk costs about the same per column whatever its length, and with few entries per column
+// adding every entry to y directly is faster.
 constexpr size_t kCscTileLds[3] = {20 * 1024, 40 * 1024, 64 * 1024};
 constexpr double kCscTileWindowGoal = 6.0;     // window slots per pixel that end the search for a larger footprint
-constexpr int kCscTileShortColumn = 9;         // columns of fewer entries leave most lanes of a step idle
+constexpr int kCscTileShortColumn = 9;         // with columns of fewer entries the direct scatter is faster at batch 1 to 3,
+constexpr int kCscTileShortestColumn = 4;      // and with columns of fewer than these at any batch
+constexpr int kCscGroupColumn = 16;            // columns of at most this many entries share a step (4 or more of them)
 
 struct CscTileChoice {
     bool ok;
@@ -992,7 +995,10 @@ static CscTileChoice choose_csc_tile(const conv_plan *plan, int batch) {
     g.inv_n_out = 1.0f / (float)sh.n_out;
     const int64_t per_axis = ((int64_t)sh.k + sh.s - 1) / sh.s;          // windows that can cover one pixel, per axis
     const int64_t column_max = per_axis * per_axis;
-    if (column_max > kCscStage || column_max < kCscTileShortColumn) return c;
+    g.column_max = (int)std::min<int64_t>(column_max, kCscStage);
+    g.spacing = sh.k;
+    g.group = g.column_max <= kCscGroupColumn ? kWave / g.column_max : 1;
+    if (column_max > kCscStage || column_max < (batch >= 4 ? kCscTileShortestColumn : kCscTileShortColumn)) return c;
     const int tj_max = (int)std::min<int64_t>(32, kCscStage / column_max);
     double best = 0.0;
     for (size_t budget : kCscTileLds) {

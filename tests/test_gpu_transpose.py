@@ -223,6 +223,8 @@ def test_transposed_march_reads_the_stored_arrays(march_everywhere):
     ((90, 77, 7, 1, 3), 2), ((90, 77, 7, 1, 3), 9), ((90, 77, 7, 1, 3), 17), ((61, 45, 5, 1, 2), 33),
     # columns no window covers (s > k), one tile line per column (k = 31), beyond the stage (k = 40)
     ((60, 60, 3, 5, 0), 4), ((70, 70, 31, 1, 15), 3), ((50, 50, 40, 1, 20), 2), ((64, 48, 17, 2, 8), 16),
+    # columns of 4 entries: on chip from batch 4 on, directly below; of 1 entry: always directly
+    ((90, 77, 2, 1, 1), 4), ((90, 77, 2, 1, 1), 3), ((90, 77, 3, 2, 1), 16), ((90, 77, 4, 2, 2), 8), ((90, 77, 2, 2, 0), 16),
     # a few lines of many tiles, many lines of one tile, several full tiles with a ragged rim
     ((3, 700, 5, 1, 2), 16), ((700, 3, 5, 1, 2), 16), ((515, 509, 7, 1, 3), 16), ((259, 263, 3, 1, 1), 1),
 ])
@@ -332,6 +334,42 @@ def test_product_from_csc_reads_the_stored_arrays():
     ref = oracle.conv(m, n, k, s, p, x, K, batch=batch).reshape(-1, batch)
     changed = np.where(np.any(np.abs(got - ref) > 1e-5 * scale + 1e-30, axis=1))[0].tolist()
     assert far in changed and int(ri[e]) in changed and int(ri[e + 1]) in changed
+    plan.close()
+
+
+@pytest.mark.parametrize("shape", [(96, 80, 3, 1, 1), (96, 80, 5, 2, 2), (60, 70, 4, 1, 2), (96, 80, 7, 2, 3), (96, 80, 2, 1, 1)])
+def test_product_from_csc_with_short_columns_reads_the_stored_arrays(shape):
+    """Short columns (k = 3, 4, 5: several columns share a step of the scatter).  One entry is
+    sent to the row two outputs further right, which the workgroup still keeps on chip but
+    which no window over that pixel has; another to the far end of y.  The result must be the
+    product with the edited matrix."""
+    import scipy.sparse as sp
+    batch = 16
+    m, n, k, s, p = shape
+    rng = np.random.default_rng(37)
+    x = rng.standard_normal(m * n * batch).astype(np.float32)
+    K = rng.standard_normal(k * k).astype(np.float32)
+    plan = build_plan_t(shape, K)
+    cp, ri, va = oracle.csc(m, n, k, s, p, K)
+    ri2 = ri.copy()
+    edits = []
+    for col, far in ((40 * n + 9, False), (41 * n + 30, True), (12 * n + 33, False)):
+        e = int(cp[col + 1]) - 1                       # the column's last entry: its largest row
+        new_row = plan.cols - 1 if far else int(ri[e]) + 2
+        assert new_row not in ri[cp[col]:cp[col + 1]]
+        ri2[e] = new_row
+        plan.col_idx[e] = new_row
+        edits += [int(ri[e]), new_row]
+    y = cs.conv_spmv_from_csc(plan, torch.from_numpy(x).to(device()), batch=batch)
+    torch.cuda.synchronize()
+    T = sp.csc_matrix((va.astype(np.float64), ri2, cp), shape=(plan.cols, plan.rows))
+    X = x.reshape(-1, batch).astype(np.float64)
+    want, scale = T @ X, abs(T) @ np.abs(X)
+    got = y.cpu().numpy().reshape(-1, batch)
+    assert np.all(np.abs(got - want) <= 1e-5 * scale + 1e-30)
+    ref = oracle.conv(m, n, k, s, p, x, K, batch=batch).reshape(-1, batch)
+    changed = set(np.where(np.any(np.abs(got - ref) > 1e-5 * scale + 1e-30, axis=1))[0].tolist())
+    assert changed == set(edits)
     plan.close()
 
 
