@@ -211,13 +211,16 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch);
 /* What conv_spmv would launch for a shape, without a plan and without a GPU
  * (host only; 16-byte-aligned operands assumed): the kernel family and the
  * launch geometry the dispatch derives.  storage: 0 = CSR of T, 1 = CSC of T
- * (the plan applies T^T), 2 = structure-aware storage; channels > 1 not with
- * storage 1.  Status as for the build calls (CONV_EINVAL, CONV_EOVERFLOW,
+ * (the plan applies T^T), 2 = structure-aware storage, 3 = CSC of T applied
+ * by conv_spmv_from_csc; channels > 1 not with storage 1 or 3.  Status as for the build calls (CONV_EINVAL, CONV_EOVERFLOW,
  * CONV_ENULL).  For tests of the host logic and for reports. */
 typedef struct conv_dispatch {
     int kernel;             /* 0 row-group scalar, 1 row-group float4, 2 LDS tile, 3 LDS march,
                                4 described rows (structure-aware), 5 rectangle path (structure-aware),
-                               6 all channels in one launch, 8 x 8 outputs per wave (structure-aware) */
+                               6 all channels in one launch, 4 x 16 outputs per wave (structure-aware),
+                               7 scatter with the sums of a tile of pixels kept on chip, 8 direct scatter
+                               (storage 3; for 7: strip x segment = pixels x lines of a tile, ring_lines_needed
+                               x lines_per_step = runs x rows of its window, lanes_per_row = columns per step) */
     int threads;            /* per workgroup */
     int64_t lds_bytes;      /* dynamic LDS per workgroup */
     int64_t workgroups;     /* that do work, over the whole launch (per channel for kernel 3) */

@@ -1207,7 +1207,8 @@ int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage
     int64_t mo, no;
     const int st = check_shape(m, n, k, s, p, &mo, &no);
     if (st != CONV_OK) return st;
-    if (batch < 1 || channels < 1 || storage < 0 || storage > 2 || (storage == 1 && channels != 1)) return CONV_EINVAL;
+    if (batch < 1 || channels < 1 || storage < 0 || storage > 3 || ((storage == 1 || storage == 3) && channels != 1))
+        return CONV_EINVAL;
     if (storage == 2 && k > 255) return CONV_EINVAL;
     const int64_t nnz = conv_nnz(m, n, k, s, p);
     // the structure-aware storage has no per-entry index, so its entry count is not limited to int32
@@ -1216,7 +1217,7 @@ int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage
     // a plan without arrays: the dispatch looks at the shape, the storage and operand alignment only
     conv_plan plan{};
     plan.shape = ConvShape{m, n, k, s, p, (int)mo, (int)no};
-    plan.transposed = storage == 1;
+    plan.transposed = storage == 1 || storage == 3;
     plan.compact = storage == 2;
     plan.channels = channels;
     plan.rows = plan.transposed ? (int64_t)m * n : mo * no;
@@ -1226,7 +1227,30 @@ int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage
     plan.max_row_nnz = per_axis * per_axis;
     conv_dispatch d{};
     const ChannelsChoice fused = choose_compact_channels(&plan, nullptr, nullptr, batch);
-    if (fused.ok) {
+    if (storage == 3) {
+        // conv_spmv_from_csc: the scatter with the sums kept on chip, or every entry added to y directly
+        const CscTileChoice tc = plan.nnz > 0 ? choose_csc_tile(&plan, batch) : CscTileChoice{};
+        if (tc.ok) {
+            d.kernel = 7;
+            d.threads = tc.waves * kWave;
+            d.lds_bytes = (int64_t)tc.lds;
+            d.workgroups = (int64_t)tc.grid.x * tc.grid.y;
+            d.strip = tc.g.tj;
+            d.segment = tc.g.ti;
+            d.ring_lines = 0;
+            d.ring_lines_needed = tc.g.wx;          // runs of the window
+            d.lines_per_step = tc.g.wy;             // rows per run
+            d.lanes_per_row = tc.g.group;           // columns that share a step
+            d.columns_per_lane = tc.vb;
+        } else {
+            d.kernel = 8;
+            d.threads = kGatherThreads;
+            d.lanes_per_row = group_width(plan.max_row_nnz);
+            d.columns_per_lane = 1;
+            const int bl = batch >= 16 ? 16 : (batch >= 4 ? 4 : 1);
+            d.workgroups = (plan.rows * d.lanes_per_row * bl + kGatherThreads - 1) / kGatherThreads;
+        }
+    } else if (fused.ok) {
         d.kernel = 6;
         d.threads = fused.ways * kWave;
         d.lds_bytes = (int64_t)fused.lds;

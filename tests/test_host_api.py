@@ -253,6 +253,51 @@ def test_dispatch_of_channel_sums_from_the_structure_aware_storage():
                 assert patch <= 16 * 64 and d["lds_bytes"] >= d["threads"] // 64 * 16 * patch
 
 
+def test_dispatch_of_the_product_from_csc_over_many_shapes():
+    """Host logic of conv_spmv_from_csc (storage 3): the on-chip scatter's tile, window and lane
+    layout stay within what its kernel assumes -- a tile line's entries within the 1024-entry
+    stage, the lanes of a wave enough for a line's column pointers, the window within 64 KiB of
+    LDS and 2^21 rows from its first one, batch columns per wave dividing 4 -- and the direct
+    scatter takes the shapes the header names."""
+    rng = np.random.default_rng(5)
+    shapes = [(1024, 1024, 7, 1, 3), (1024, 1024, 3, 1, 1), (224, 224, 7, 2, 3), (4096, 4096, 11, 4, 5), (56, 56, 1, 1, 0),
+              (300, 300, 255, 3, 100), (700, 900, 40, 1, 20), (56, 56, 2, 2, 0), (3, 3, 9, 2, 3), (20, 200000, 3, 1, 1),
+              (64, 64, 33, 1, 16), (64, 64, 32, 1, 16), (500, 500, 64, 2, 10)]
+    for _ in range(400):
+        k, s, p = int(rng.integers(1, 40)), int(rng.integers(1, 6)), int(rng.integers(0, 12))
+        m, n = (int(v) for v in rng.integers(max(1, k - 2 * p), 3000, size=2))
+        if oracle.nnz_closed(m, n, k, s, p) < 2 ** 31:
+            shapes.append((m, n, k, s, p))
+    seen = set()
+    for m, n, k, s, p in shapes:
+        per_axis = -(-k // s)
+        mo, no = oracle.out_shape(m, n, k, s, p)
+        for batch in (1, 2, 3, 4, 5, 8, 9, 16, 48):
+            d = _dispatch(m, n, k, s, p, batch, 3)
+            seen.add(d["kernel"])
+            if per_axis ** 2 > 1024 or per_axis ** 2 < (4 if batch >= 4 else 9):
+                assert d["kernel"] == 8, (m, n, k, s, p, batch)
+            if d["kernel"] == 8:
+                assert d["threads"] == 256 and d["workgroups"] >= 1
+                continue
+            assert d["kernel"] == 7
+            ti, tj, wx, wy, vb, waves = d["segment"], d["strip"], d["ring_lines_needed"], d["lines_per_step"], d["columns_per_lane"], d["threads"] // 64
+            assert 1 <= tj <= 32 and 1 <= ti <= 64 and tj * per_axis ** 2 <= 1024
+            assert wx == min((ti + k - 2) // s + 1, mo) and wy == min((tj + k - 2) // s + 1, no)
+            assert (wx - 1) * no + wy <= 1 << 21 and wx * wy < 1 << 16
+            assert vb in (1, 2, 4) and waves in (1, 2, 4) and vb * waves <= 16
+            assert (vb == batch) if batch < 3 else vb == 4
+            stage = (tj * per_axis ** 2 + 1) // 2 * 2
+            assert d["lds_bytes"] == 16 * stage + 4 * ((ti * (tj + 1) + 3) // 4 * 4) + wx * wy * vb * waves * 4 <= 64 * 1024
+            tiles = -(-m // ti) * -(-n // tj)
+            assert d["workgroups"] == tiles * min(-(-batch // (vb * waves)), 65535)
+            group = d["lanes_per_row"]
+            assert group == (64 // per_axis ** 2 if per_axis ** 2 <= 16 else 1) and group * min(per_axis ** 2, 64) <= 64
+    assert seen == {7, 8}
+    with pytest.raises(cs.ConvError):
+        _dispatch(64, 64, 3, 1, 1, 16, 3, 2)          # no channels with the column-compressed arrays
+
+
 def test_dispatch_of_the_named_workloads():
     want = {"small_32_k3": 0, "strided_256_k5_b64": 2, "headline_1024_k7_b1": 3, "headline_1024_k7_b16": 3,
             "cnn_224_k3_b256": 2, "padheavy_512_k9_s3": 0, "padheavy_4096_k11_s4_b4": 3}
@@ -267,7 +312,7 @@ def test_dispatch_of_the_named_workloads():
     # several channels: the LDS tile kernel is not used (one launch per channel would not pay)
     assert _dispatch(224, 224, 3, 1, 1, 16, 0, 64)["kernel"] == 1
     assert _dispatch(1024, 1024, 7, 1, 3, 16, 0, 3)["kernel"] == 3
-    for bad in [(4, 4, 9, 1, 0, 1, 0, 1), (8, 8, 3, 1, 1, 0, 0, 1), (8, 8, 3, 1, 1, 1, 3, 1), (8, 8, 3, 1, 1, 1, 1, 2),
+    for bad in [(4, 4, 9, 1, 0, 1, 0, 1), (8, 8, 3, 1, 1, 0, 0, 1), (8, 8, 3, 1, 1, 1, 4, 1), (8, 8, 3, 1, 1, 1, 1, 2),
                 (300, 300, 256, 1, 0, 1, 2, 1)]:
         with pytest.raises(cs.ConvError):
             cs.conv_dispatch_info(*bad)
