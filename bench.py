@@ -8,8 +8,10 @@ paper Section 2); the build is timed in the same run and reported beside it.
 
 Prints ONE JSON line: effective HBM GB/s of the apply (model bytes = entries *
 (index + value) + row_ptr + x once + y once, divided by the time per step),
-useful MAC/s, build time, the roofline of the apply kernel (HIP events around
-single launches on the launch stream) and the CPU oracle timed on this host.
+useful MAC/s, build time, the roofline of the apply kernel (HIP events on the
+launch stream), a table of all named configurations and the CPU oracle timed on
+this host.  Everything the headline figures rest on is timed on ONE stream,
+after the device has settled (see precondition).
 """
 from __future__ import annotations
 
@@ -209,12 +211,82 @@ def sweep_main(args):
     print(json.dumps(out))
 
 
+def event_times_ms(fn, count, stream):
+    """`count` calls of fn, each between its own pair of HIP events on `stream`: sorted durations in ms."""
+    import torch
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(count)]
+    for a, b in evs:
+        a.record(stream)
+        fn()
+        b.record(stream)
+    torch.cuda.synchronize()
+    return sorted(a.elapsed_time(b) for a, b in evs)
+
+
+def precondition(fn, stream, cap_s=0.5, batch_len=50, tol=0.01):
+    """Run fn until the device has settled: after an idle period the shader clock ramps for some
+    tens of milliseconds (measured: 1.4 -> 2.4 GHz over the first ~250 launches of the headline
+    apply, whose duration follows it, 133 -> 112 us), so launches are issued in batches of 50, each
+    between its own events, until the median of a batch is within 1 % of the batch before, for at
+    most half a second.  Independent of --warmup.  Returns (launches, last median in ms)."""
+    t0 = time.perf_counter()
+    launches, prev = 0, None
+    while True:
+        med = event_times_ms(fn, batch_len, stream)[batch_len // 2]
+        launches += batch_len
+        if prev is not None and abs(med - prev) <= tol * prev and launches >= 3 * batch_len:
+            return launches, med
+        if time.perf_counter() - t0 > cap_s:
+            return launches, med
+        prev = med
+
+
+LLC_BYTES = 256 * 1024 * 1024     # Infinity Cache: a working set below this does not measure HBM
+
+
+def config_entry(cs, oracle, workloads, name, dev, stream, launches=60):
+    """One named workload, single stream: variant, median / min us of event-bracketed launches after
+    the device has settled, model bytes and rate, useful MAC/s, error against the oracle."""
+    import numpy as np
+    import torch
+    w = workloads.WORKLOADS[name]
+    m, n, k, s, p = w.shape
+    x_h, K_h = workloads.make(w)
+    x = torch.from_numpy(x_h).to(dev)
+    plan = cs.conv_csr_build(m, n, k, s, p, torch.from_numpy(K_h).to(dev))
+    y = torch.empty(plan.rows * w.batch, dtype=torch.float32, device=dev)
+    fn = lambda: cs.conv_spmv(plan, x, y, batch=w.batch)
+    pre, _ = precondition(fn, stream, cap_s=0.25)
+    ms = event_times_ms(fn, launches, stream)
+    med, mn = ms[len(ms) // 2], ms[0]
+    ref, scale = oracle.conv(m, n, k, s, p, x_h, K_h, batch=w.batch, want_scale=True)
+    got = y.cpu().numpy().astype(np.float64)
+    err = np.abs(got - ref.astype(np.float64))
+    live = scale > 0
+    rel = err[live] / np.maximum(np.abs(ref[live]).astype(np.float64), 1e-300)
+    model = plan.model_bytes(w.batch)
+    out = {
+        "shape": [m, n, k, s, p], "batch": w.batch, "variant": plan.variant(w.batch),
+        "us_median": med * 1e3, "us_min": mn * 1e3, "launches": launches, "precondition_launches": pre,
+        "model_bytes": model, "model_gbs": model / (med * 1e-3) / 1e9,
+        "frac_of_hbm_peak": model / (med * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "cache_resident": bool(model < LLC_BYTES),
+        "useful_mac_per_s": plan.nnz * w.batch / (med * 1e-3),
+        "max_err_over_scale": float(np.max(err[live] / scale[live])) if np.any(live) else 0.0,
+        "normwise_err": float(np.max(err) / max(float(np.max(np.abs(ref))), 1e-300)),
+        "rel_err_vs_ref": {"median": float(np.median(rel)), "p99": float(np.quantile(rel, 0.99)), "max": float(np.max(rel))},
+    }
+    plan.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=300)
-    ap.add_argument("--streams", type=int, default=3, help="HIP streams the timed applies take turns on")
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--streams", type=int, default=3,
+                    help="HIP streams of the extra 'applies in flight' measurement (0 or 1: skip it)")
     ap.add_argument("--workload", default=None,
                     help="name in workloads.WORKLOADS (default: the headline), or densenet121_sweep")
     ap.add_argument("--batch", type=int, default=1, help="batch of the densenet121_sweep workload")
@@ -225,6 +297,7 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--no-side-paths", action="store_true",
                     help="skip the brief timing of the structure-aware storage and of T^T on the same workload")
+    ap.add_argument("--no-configs", action="store_true", help="skip the per-configuration table of the named workloads")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this path is built and timed on a single MI355X "
@@ -282,58 +355,61 @@ def main():
     build_med = sorted(build_ms)[len(build_ms) // 2]
 
     y = torch.empty(plan.rows * w.batch, dtype=torch.float32, device=dev)
+    apply_once = lambda: cs.conv_spmv(plan, x, y, batch=w.batch)
 
-    # ---- warm-up, then exactly K steps between two synchronisations.  The K applies are
-    # independent of each other (a stream of batches through one T), so they are issued in
-    # turn on three HIP streams, each with its own output buffer: the start of one apply then
-    # overlaps the tails of the ones before it (three measured better than two or four: 92,
-    # 99.5 and 97 us per apply).  The same K applies issued on a single stream are timed as
-    # well and reported as ms_per_step_one_stream.
-    n_streams = max(1, args.streams)
-    side = [torch.cuda.Stream() for _ in range(n_streams)] if n_streams > 1 else [stream]
-    ys = [y] + [torch.empty_like(y) for _ in range(n_streams - 1)]
+    # ---- the device settles first (clock ramp after idle), whatever --warmup says
+    pre_launches, pre_median = precondition(apply_once, stream)
 
-    def run_steps(count, streams):
-        for q in streams:
-            q.wait_stream(stream)
-        for i in range(count):
-            j = i % len(streams)
-            cs.conv_spmv(plan, x, ys[j], batch=w.batch, stream=streams[j])
-        for q in streams:
-            stream.wait_stream(q)
-
-    run_steps(args.warmup, side)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    run_steps(args.steps, side)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ms_per_step = wall * 1e3 / args.steps
-
-    # ---- the same K applies on the launch stream alone, bracketed by two HIP events recorded on
-    # that stream: elapsed / K is the kernel's average launch duration over the timed region
-    run_steps(args.warmup, [stream])
+    # ---- W warm-up steps, then exactly K steps on ONE stream between two synchronisations.  Two HIP
+    # events on that stream bracket the K launches: elapsed / K is the kernel's average launch
+    # duration over the timed region, the figure of the roofline.
+    for _ in range(args.warmup):
+        apply_once()
     torch.cuda.synchronize()
     r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     r0.record(stream)
-    run_steps(args.steps, [stream])
+    for _ in range(args.steps):
+        apply_once()
     r1.record(stream)
     torch.cuda.synchronize()
-    ms_per_step_one_stream = (time.perf_counter() - t0) * 1e3 / args.steps
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
     region_avg = r0.elapsed_time(r1) / args.steps
 
     # ---- single launches, each between its own pair of events (includes the gap between two
     # launches, a few microseconds): median and minimum
-    n_ev = min(args.steps, 100)
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_ev)]
-    for a, b in evs:
-        a.record(stream)
-        cs.conv_spmv(plan, x, y, batch=w.batch)
-        b.record(stream)
-    torch.cuda.synchronize()
-    kern_ms = sorted(a.elapsed_time(b) for a, b in evs)
+    kern_ms = event_times_ms(apply_once, max(min(args.steps, 100), 20), stream)
     kern_avg = sum(kern_ms) / len(kern_ms)
+
+    # ---- extra: the same applies issued in turn on several streams (independent batches through one
+    # T, each stream with its own y).  The applies in flight then share T through the L2 and the
+    # Infinity Cache, so this is a throughput of a stream of batches, NOT an HBM bandwidth figure.
+    overlapped = None
+    if args.streams > 1:
+        side = [torch.cuda.Stream() for _ in range(args.streams)]
+        ys = [torch.empty_like(y) for _ in range(args.streams)]
+
+        def run_steps(count):
+            for q in side:
+                q.wait_stream(stream)
+            for i in range(count):
+                j = i % len(side)
+                cs.conv_spmv(plan, x, ys[j], batch=w.batch, stream=side[j])
+            for q in side:
+                stream.wait_stream(q)
+
+        run_steps(max(args.warmup, 3 * args.streams))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run_steps(args.steps)
+        torch.cuda.synchronize()
+        ov_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        overlapped = {"streams": args.streams, "ms_per_apply": ov_ms,
+                      "model_bytes_over_time_gbs": plan.model_bytes(w.batch) / (ov_ms * 1e-3) / 1e9,
+                      "note": "applies in flight on several streams share T in the L2 / Infinity Cache: "
+                              "throughput of a stream of batches, not an HBM bandwidth measurement"}
+        del ys
 
     # ---- a plain copy that moves the same number of bytes (half read, half written): the
     # streaming ceiling of this machine, and the kernel of known size that calibrates the
@@ -363,16 +439,22 @@ def main():
                    "SpMM effective HBM GB/s at 1024^2, k=7, batch 16 (model bytes / time per apply)"
                    if w.name == workloads.HEADLINE else "SpMV/SpMM effective GB/s (model bytes / time per apply)"),
         "value": gbs, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "ms_per_step_one_stream": ms_per_step_one_stream, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.name, "m": m, "n": n, "k": k, "s": s, "p": p, "batch": w.batch,
                    "nnz": plan.nnz, "rows": plan.rows, "cols": plan.cols,
-                   "apply_variant": plan.variant(w.batch), "streams": n_streams,
+                   "apply_variant": plan.variant(w.batch), "streams": 1,
                    "matrix": "T (row descriptors + k*k table)" if args.compact
                    else ("T^T (CSC of T)" if args.transposed else "T (CSR)")},
+        "timing": "one stream; %d launches until the device had settled (median of 50 within 1 %% of the 50 before, "
+                  "at most 0.5 s), %d warm-up, %d timed between two synchronisations" % (pre_launches, args.warmup, args.steps),
+        "precondition_launches": pre_launches, "precondition_last_median_ms": pre_median,
         "pct_of_hbm_peak": 100.0 * gbs / HBM_PEAK_GBS,
         "useful_mac_per_s": plan.nnz * w.batch / (ms_per_step * 1e-3),
         "model_bytes": model_bytes,
+        "error_criterion": "per output |y - ref| <= 1e-5 * sum_e |vals[e]| |x[col_idx[e]]| (componentwise backward "
+                           "error of the dot product) and max|y - ref| <= 1e-5 * max|ref|; the plain per-output "
+                           "relative error is reported per configuration as rel_err_vs_ref",
         "build_ms": build_med,
         "build_over_apply": build_med / ms_per_step,
         "copy_gbs_same_bytes": copy_gbs,
@@ -384,8 +466,11 @@ def main():
                      "timing": "two HIP events on the launch stream around the %d timed launches, elapsed / %d"
                                % (args.steps, args.steps),
                      "single_launch_ms_avg": kern_avg, "single_launch_ms_median": kern_ms[len(kern_ms) // 2],
-                     "single_launch_ms_min": kern_ms[0]},
+                     "single_launch_ms_min": kern_ms[0],
+                     "frac_from_single_launch_median": model_bytes / (kern_ms[len(kern_ms) // 2] * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
+    if overlapped is not None:
+        out["applies_in_flight_on_several_streams"] = overlapped
     if args.compact:
         # 8 bytes per row instead of 8 per entry: the multiply-adds, not the bytes, bound this kernel
         tflops = 2.0 * plan.nnz * w.batch / (region_avg * 1e-3) / 1e12
@@ -449,10 +534,20 @@ def main():
                          "useful_tflops": 2.0 * pl.nnz * cc * w.batch / (avg * 1e-3) / 1e12}
             pl.close()
         out["side_paths"] = side
+    plan.close()
+    del plan, y
+    if not (args.compact or args.transposed or args.no_configs) and w.name == workloads.HEADLINE:
+        # every named configuration, single stream, each against the oracle
+        import oracle
+        oracle.build()
+        names = {"1": "small_32_k3", "2": "strided_256_k5_b64", "3a": "headline_1024_k7_b1",
+                 "3b": "headline_1024_k7_b16", "4": "cnn_224_k3_b256", "5a": "padheavy_512_k9_s3",
+                 "5b": "padheavy_4096_k11_s4_b4"}
+        out["configs"] = {tag: dict(config_entry(cs, oracle, workloads, nm, dev, stream), workload=nm)
+                          for tag, nm in names.items()}
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, x_h, K_h, args.transposed)
         out["gpu_over_cpu"] = out["useful_mac_per_s"] / 1e9 / out["cpu_baseline"]["value"]
-    plan.close()
     print(json.dumps(out))
 
 

@@ -67,8 +67,12 @@ int64_t conv_nnz(int m, int n, int k, int s, int p);
  * they must outlive it and must not be modified while an apply is in flight.
  * The plan itself owns a small device table (the two per-axis prefix sums of
  * the row-length factors, (m_out + n_out + 2) int32), allocated here with
- * hipMalloc and released by conv_plan_destroy.
- * On error nothing is enqueued and *plan_out is left NULL. */
+ * hipMalloc and released by conv_plan_destroy (both synchronise the device).
+ * Argument errors (CONV_EINVAL, CONV_ENULL, CONV_EOVERFLOW, CONV_ENOMEM) are
+ * found before anything is enqueued.  CONV_EHIP means that one of this call's
+ * own launches failed: earlier launches of the call may already be enqueued.
+ * An error that other code left in the runtime's last-error slot is neither
+ * reported nor cleared.  On any error *plan_out is left NULL. */
 int conv_csr_build(int m, int n, int k, int s, int p,
                    const float *kernel_dev,
                    int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev,
@@ -169,7 +173,9 @@ int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream);
  *   batch : number of vectors sharing T (1 = SpMV).
  * The kernels read row_ptr, col_idx and vals as stored: the result is the
  * product with whatever the three arrays hold, provided row_ptr is still
- * non-decreasing with row lengths <= k*k and every col_idx is in [0, m*n).
+ * non-decreasing, no row is longer than the longest row the build wrote (k*k
+ * for T; ceil(k/s)^2 for the T^T of conv_csc_build) and every col_idx is in
+ * [0, number of columns).
  * fp32 multiply-add, summation order unspecified but fixed: repeated calls
  * give bit-identical results.  (A plan with several channels runs either
  * one kernel that sums the channels in a fixed order, or one kernel per
@@ -188,9 +194,10 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
  * conv_spmv on the CSR plan of the same T up to the order of the additions,
  * which here depends on timing: repeated calls agree to rounding, not bit for
  * bit.  The arrays are read as stored: every row_idx must be in
- * [0, m_out*n_out), col_ptr non-decreasing, and the row indices of one column
- * pairwise different, as conv_csc_build writes them (a row stored twice in
- * one column may lose one of its two contributions). */
+ * [0, m_out*n_out), col_ptr non-decreasing, no column longer than ceil(k/s)^2
+ * entries (the longest conv_csc_build writes), and the row indices of one
+ * column pairwise different, as conv_csc_build writes them (a row stored twice
+ * in one column may lose one of its two contributions). */
 int conv_spmv_from_csc(const conv_plan *plan, const float *x_dev, float *y_dev, int batch, void *stream);
 
 /* Shape and size queries on a plan (host only).  conv_plan_is_transposed
@@ -220,15 +227,16 @@ typedef struct conv_dispatch {
                                6 all channels in one launch, 4 x 16 outputs per wave (structure-aware),
                                7 scatter with the sums of a tile of pixels kept on chip, 8 direct scatter
                                (storage 3; for 7: strip x segment = pixels x lines of a tile, ring_lines_needed
-                               x lines_per_step = runs x rows of its window, lanes_per_row = columns per step) */
+                               x lines_per_step = runs x rows of its window, lanes_per_row = columns per step),
+                               9 LDS march with one lane per row */
     int threads;            /* per workgroup */
     int64_t lds_bytes;      /* dynamic LDS per workgroup */
     int64_t workgroups;     /* that do work, over the whole launch (per channel for kernel 3) */
-    int strip;              /* output columns per strip / tile line (kernels 2-6), else 0 */
-    int segment;            /* output lines per workgroup (kernels 2-6), else 0 */
-    int ring_lines;         /* LDS ring lines (kernels 3-5; 0 = no ring) */
+    int strip;              /* output columns per strip / tile line (kernels 2-6, 9), else 0 */
+    int segment;            /* output lines per workgroup (kernels 2-6, 9), else 0 */
+    int ring_lines;         /* LDS ring lines (kernels 3-5, 9; 0 = no ring) */
     int ring_lines_needed;  /* lines a step keeps resident (<= ring_lines when there is a ring) */
-    int lines_per_step;     /* output lines per step (kernels 3-5) */
+    int lines_per_step;     /* output lines per step (kernels 3-5, 9) */
     int lanes_per_row;      /* lanes that share a row of the matrix */
     int columns_per_lane;   /* batch columns per lane */
 } conv_dispatch;
@@ -263,14 +271,23 @@ int conv_multi_create(int n, const conv_plan *const *plans, const float *const *
 int conv_multi_apply(const conv_multi *multi, void *stream);
 int conv_multi_destroy(conv_multi *multi);   /* NULL is accepted */
 
-/* Tuning knob of the apply dispatch (process-wide, thread-safe).  conv_spmv
- * uses its persistent "marching" kernel only when the problem splits into at
- * least `jobs` strip segments (64 or 32 output columns x 8 output lines x one
- * block of batch columns); smaller problems cannot fill the chip that way and
- * go to the row-group kernels.  Default 256.  Returns the previous value, or
- * CONV_EINVAL for jobs < 1.  The result of conv_spmv does not depend on it
- * beyond the summation order. */
-int conv_set_march_min_jobs(int jobs);
+/* ---------------------------------------------------------------------------
+ * Test hooks.  Not part of the product interface: they exist so that the tests
+ * can drive the persistent "marching" kernels on shapes far smaller than the
+ * ones the dispatch would give them.
+ *
+ * conv_spmv uses a marching kernel only when the problem splits into at least
+ * `jobs` strip segments (64 or 32 output columns x 8 output lines x one block
+ * of batch columns); smaller problems cannot fill the chip that way and go to
+ * the row-group kernels.  The threshold is a field of the plan (default 256);
+ * conv_plan_set_march_min_jobs changes it for that plan only and returns the
+ * previous value (CONV_EINVAL for jobs < 1, CONV_ENULL without a plan).  Not
+ * thread-safe against a concurrent conv_spmv on the same plan.  The result of
+ * conv_spmv does not depend on it beyond the summation order.
+ * conv_test_dispatch_info is conv_dispatch_info with that threshold given. */
+int conv_plan_set_march_min_jobs(conv_plan *plan, int jobs);
+int conv_test_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage, int channels,
+                            int march_min_jobs, conv_dispatch *out);
 
 #ifdef __cplusplus
 }

@@ -15,7 +15,7 @@ from .binding import (  # noqa: F401
     conv_csr_build_channels,
     conv_nnz,
     conv_out_shape,
-    conv_set_march_min_jobs,
+    conv_plan_set_march_min_jobs,
     conv_spmv,
     conv_spmv_from_csc,
     conv_strerror,

@@ -19,7 +19,7 @@ _lib = None
 EXPORTS = (
     "conv_out_shape", "conv_nnz", "conv_csr_build", "conv_spmv", "conv_plan_shape",
     "conv_spmv_variant", "conv_plan_destroy", "conv_strerror", "conv_last_hip_error",
-    "conv_set_march_min_jobs", "conv_update_kernel",
+    "conv_plan_set_march_min_jobs", "conv_test_dispatch_info", "conv_update_kernel",
     "conv_multi_create", "conv_multi_apply", "conv_multi_destroy",
     "conv_csc_build", "conv_plan_is_transposed",
     "conv_compact_build", "conv_plan_is_compact",
@@ -104,8 +104,10 @@ def _load():
         lib.conv_multi_destroy.restype = i
         lib.conv_update_kernel.argtypes = [vp, vp, vp]
         lib.conv_update_kernel.restype = i
-        lib.conv_set_march_min_jobs.argtypes = [i]
-        lib.conv_set_march_min_jobs.restype = i
+        lib.conv_plan_set_march_min_jobs.argtypes = [vp, i]
+        lib.conv_plan_set_march_min_jobs.restype = i
+        lib.conv_test_dispatch_info.argtypes = [i] * 9 + [ctypes.POINTER(ConvDispatch)]
+        lib.conv_test_dispatch_info.restype = i
         _lib = lib
         return lib
 
@@ -114,18 +116,23 @@ def conv_strerror(status: int) -> str:
     return _load().conv_strerror(int(status)).decode()
 
 
-def conv_set_march_min_jobs(jobs: int) -> int:
-    """Set the dispatch knob; returns the previous value."""
-    prev = _load().conv_set_march_min_jobs(int(jobs))
+def conv_plan_set_march_min_jobs(plan, jobs: int) -> int:
+    """Test hook: the plan's threshold for the marching kernels; returns the previous value."""
+    prev = _load().conv_plan_set_march_min_jobs(plan._handle, int(jobs))
     if prev < 0:
-        raise ConvError(prev, "conv_set_march_min_jobs(%r)" % (jobs,))
+        raise ConvError(prev, "conv_plan_set_march_min_jobs(%r)" % (jobs,))
     return prev
 
 
-def conv_dispatch_info(m, n, k, s, p, batch=1, storage=0, channels=1) -> ConvDispatch:
-    """What conv_spmv would launch for this shape (host only, no GPU needed)."""
+def conv_dispatch_info(m, n, k, s, p, batch=1, storage=0, channels=1, march_min_jobs=None) -> ConvDispatch:
+    """What conv_spmv would launch for this shape (host only, no GPU needed).  march_min_jobs:
+    the test hook's threshold (conv_test_dispatch_info) instead of the default."""
     d = ConvDispatch()
-    st = _load().conv_dispatch_info(m, n, k, s, p, int(batch), int(storage), int(channels), ctypes.byref(d))
+    if march_min_jobs is None:
+        st = _load().conv_dispatch_info(m, n, k, s, p, int(batch), int(storage), int(channels), ctypes.byref(d))
+    else:
+        st = _load().conv_test_dispatch_info(m, n, k, s, p, int(batch), int(storage), int(channels),
+                                             int(march_min_jobs), ctypes.byref(d))
     if st != 0:
         raise ConvError(st, "conv_dispatch_info%r" % ((m, n, k, s, p, batch, storage, channels),))
     return d
@@ -151,6 +158,18 @@ def _stream_handle(stream):
     if stream is None:
         stream = torch.cuda.current_stream()
     return ctypes.c_void_p(stream.cuda_stream), stream
+
+
+def _on_stream(stream, *tensors):
+    """Tensors that this binding allocated (on torch's current stream) and that the library's
+    kernels use on `stream`: tell the caching allocator, so that a block is not handed to other
+    work while those kernels may still touch it."""
+    import torch
+    if stream is None or stream == torch.cuda.current_stream():
+        return
+    for t in tensors:
+        if t is not None and t.numel():
+            t.record_stream(stream)
 
 
 class ConvPlan:
@@ -231,6 +250,7 @@ def conv_csr_build(m, n, k, s, p, kernel, stream=None, _transposed=False) -> Con
                 col_idx.data_ptr(), vals.data_ptr(), sh, ctypes.byref(handle))
     if st != 0:
         raise ConvError(st, "%s%r" % ("conv_csc_build" if _transposed else "conv_csr_build", (m, n, k, s, p)))
+    _on_stream(stream, row_ptr, col_idx, vals)
     return ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, row_ptr, col_idx, vals, kernel, transposed=_transposed)
 
 
@@ -257,6 +277,7 @@ def conv_csr_build_channels(m, n, k, s, p, kernels, channels, stream=None) -> Co
                                          col_idx.data_ptr(), vals.data_ptr(), sh, ctypes.byref(handle))
     if st != 0:
         raise ConvError(st, "conv_csr_build_channels%r" % ((m, n, k, s, p, channels),))
+    _on_stream(stream, row_ptr, col_idx, vals)
     plan = ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, row_ptr, col_idx, vals, kernels)
     plan.channels = int(channels)
     return plan
@@ -285,6 +306,7 @@ def conv_compact_build(m, n, k, s, p, kernel, stream=None, channels: int = 1) ->
                                              ktab.data_ptr(), sh, ctypes.byref(handle))
     if st != 0:
         raise ConvError(st, "conv_compact_build%r" % ((m, n, k, s, p),))
+    _on_stream(stream, row_desc, ktab)
     plan = ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, None, None, None, kernel)
     plan.compact = True
     plan.channels = int(channels)
@@ -319,6 +341,7 @@ def conv_spmv(plan: ConvPlan, x, y=None, batch: int = 1, stream=None):
         raise ValueError("x has %d elements, expected m*n*batch = %d" % (x.numel(), plan.cols * batch))
     if y is None:
         y = torch.empty(plan.rows * max(batch, 1), dtype=torch.float32, device=x.device)
+        _on_stream(stream, y)
     elif not (y.is_cuda and y.dtype == torch.float32 and y.is_contiguous()
               and y.numel() == plan.rows * batch):
         raise ValueError("y must be a contiguous float32 device tensor with m_out*n_out*batch elements")
@@ -344,6 +367,7 @@ def conv_spmv_from_csc(plan: ConvPlan, x, y=None, batch: int = 1, stream=None):
     out = plan.m_out * plan.n_out * batch
     if y is None:
         y = torch.empty(out, dtype=torch.float32, device=x.device)
+        _on_stream(stream, y)
     elif not (y.is_cuda and y.dtype == torch.float32 and y.is_contiguous() and y.numel() == out):
         raise ValueError("y must be a contiguous float32 device tensor with m_out*n_out*batch elements")
     with torch.cuda.device(x.device):

@@ -52,6 +52,7 @@ struct MarchGeom {
     float inv_n;          // 1.0f / n
     int accum;            // 1: add to y instead of storing (later channels of a multi-channel sum)
     int col_blocks;       // blocks of batch columns (4*NV each, or 1): batch / (4*NV), or batch
+    int max_row;          // most entries a row of the matrix has
 };
 
 // NV: float4 column chunks per lane (NV planes in LDS, 4*NV batch columns per

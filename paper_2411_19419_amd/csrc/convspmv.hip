@@ -6,12 +6,14 @@
 
 #include <algorithm>
 #include <atomic>
+#include <mutex>
 #include <cstdio>
 #include <cstring>
 #include <new>
 
 #include "apply_kernels.h"
 #include "apply_march_kernel.h"
+#include "apply_stage_march_kernel.h"
 #include "apply_tile_kernel.h"
 #include "build_kernels.h"
 #include "compact_channels_kernel.h"
@@ -30,6 +32,26 @@ inline bool hip_ok(hipError_t e) {
 }
 
 constexpr int64_t kInt32Limit = 2147483647LL;   // largest int32
+
+// Fewer strip segments than this cannot fill the chip with persistent workgroups; the row-group
+// kernels take such problems.  A plan carries its own copy (conv_plan_set_march_min_jobs).
+constexpr int kMarchMinJobs = 256;
+
+// Attributes launch failures to this call only: the runtime's last-error slot may already
+// hold an error of other code in the process (it is sticky until somebody reads it).  The
+// slot is peeked before the first launch and after the last; an error that was there before
+// is neither reported as ours nor cleared.
+struct LaunchScope {
+    hipError_t before;
+    LaunchScope() : before(hipPeekAtLastError()) {}
+    bool ok() const {
+        const hipError_t after = hipPeekAtLastError();
+        if (after == hipSuccess || after == before) return true;
+        g_last_hip_error = (int)after;
+        (void)hipGetLastError();      // ours: take it out of the slot
+        return false;
+    }
+};
 
 // Theorem 2.1, output extent along one axis (0 = precondition violated).
 int64_t out_extent(int64_t extent, int64_t k, int64_t s, int64_t p) {
@@ -66,6 +88,7 @@ struct conv_plan {
     const int *col_idx;       // borrowed, device
     float *vals;              // borrowed, device (rewritten by conv_update_kernel)
     int *axis_tab;            // owned, device: the two per-axis prefix tables of the build
+    int march_min_jobs;       // fewest strip segments for which the marching kernel is used
     int device;
     bool transposed;          // the arrays hold T^T (CSC of T): rows = m*n, cols = m_out*n_out
     int channels;             // input channels sharing row_ptr / col_idx; vals holds `channels` arrays of nnz
@@ -125,11 +148,10 @@ bool launch_fill(const conv_plan *plan, const float *kernel_dev, int *idx_dev, f
     return false;
 }
 
+// Argument and size checks shared by the CSR / CSC builds; fills the size fields of *plan.
 template <bool TR>
-int build_impl(int m, int n, int k, int s, int p, int channels, const float *kernel_dev, int32_t *ptr_dev,
-               int32_t *idx_dev, float *vals_dev, void *stream, conv_plan **plan_out) {
-    if (!plan_out) return CONV_ENULL;
-    *plan_out = nullptr;
+int build_check(int m, int n, int k, int s, int p, int channels, const float *kernel_dev, const int32_t *ptr_dev,
+                const int32_t *idx_dev, const float *vals_dev, conv_plan *plan, int64_t *rp_blocks_out) {
     int64_t mo, no;
     int st = check_shape(m, n, k, s, p, &mo, &no);
     if (st != CONV_OK) return st;
@@ -150,45 +172,63 @@ int build_impl(int m, int n, int k, int s, int p, int channels, const float *ker
     const int64_t rp_blocks = l1 * ((l2 + kRowPtrThreads - 1) / kRowPtrThreads);
     if (fill_blocks > kInt32Limit || rp_blocks > kInt32Limit) return CONV_EOVERFLOW;
     if (!ptr_dev || !kernel_dev || (nnz > 0 && (!idx_dev || !vals_dev))) return CONV_ENULL;
-
-    conv_plan *plan = new (std::nothrow) conv_plan;
-    if (!plan) return CONV_ENOMEM;
+    *plan = conv_plan{};
     plan->shape = ConvShape{m, n, k, s, p, (int)mo, (int)no};
     plan->rows = rows;
     plan->cols = cols;
     plan->nnz = nnz;
     const int per_axis = TR ? (k + s - 1) / s : k;
     plan->max_row_nnz = per_axis * per_axis;
+    plan->march_min_jobs = kMarchMinJobs;
+    plan->transposed = TR;
+    plan->channels = channels;
+    *rp_blocks_out = rp_blocks;
+    return CONV_OK;
+}
+
+// The build kernels of a checked plan whose axis_tab points at (lines + rows per line + 2) ints.
+template <bool TR>
+void build_enqueue(const conv_plan *plan, const float *kernel_dev, int32_t *ptr_dev, int32_t *idx_dev,
+                   float *vals_dev, int64_t rp_blocks, hipStream_t q) {
+    const int k = plan->shape.k;
+    axis_prefix_kernel<TR><<<2, kAxisThreads, 0, q>>>(plan->shape, plan->axis_tab);
+    // the staged fill writes row_ptr on its way; otherwise (no entries, or rows too long for it) its own kernel does
+    bool have_row_ptr = false;
+    if (plan->nnz > 0) have_row_ptr = launch_fill<true, TR>(plan, kernel_dev, idx_dev, vals_dev, q, ptr_dev);
+    if (!have_row_ptr)
+        row_ptr_kernel<TR><<<(unsigned)rp_blocks, kRowPtrThreads, 0, q>>>(plan->shape, plan->axis_tab, ptr_dev);
+    if (plan->nnz > 0) {
+        for (int ch = 1; ch < plan->channels; ++ch)      // the other channels share the indices: values only
+            launch_fill<false, TR>(plan, kernel_dev + (size_t)ch * k * k, nullptr, vals_dev + (size_t)ch * plan->nnz, q);
+    }
+}
+
+template <bool TR>
+int build_impl(int m, int n, int k, int s, int p, int channels, const float *kernel_dev, int32_t *ptr_dev,
+               int32_t *idx_dev, float *vals_dev, void *stream, conv_plan **plan_out) {
+    if (!plan_out) return CONV_ENULL;
+    *plan_out = nullptr;
+    conv_plan checked;
+    int64_t rp_blocks = 0;
+    const int st = build_check<TR>(m, n, k, s, p, channels, kernel_dev, ptr_dev, idx_dev, vals_dev, &checked, &rp_blocks);
+    if (st != CONV_OK) return st;
+    conv_plan *plan = new (std::nothrow) conv_plan(checked);
+    if (!plan) return CONV_ENOMEM;
     plan->row_ptr = ptr_dev;
     plan->col_idx = idx_dev;
     plan->vals = vals_dev;
-    plan->axis_tab = nullptr;
-    plan->device = 0;
-    plan->transposed = TR;
-    plan->channels = channels;
-    plan->compact = false;
-    plan->desc = nullptr;
-    plan->ktab = nullptr;
     if (!hip_ok(hipGetDevice(&plan->device))) {
         delete plan;
         return CONV_EHIP;
     }
+    const int64_t l1 = TR ? m : plan->shape.m_out, l2 = TR ? n : plan->shape.n_out;
     if (!hip_ok(hipMalloc((void **)&plan->axis_tab, sizeof(int) * (size_t)(l1 + l2 + 2)))) {
         delete plan;
         return CONV_ENOMEM;
     }
-    hipStream_t q = (hipStream_t)stream;
-    axis_prefix_kernel<TR><<<2, kAxisThreads, 0, q>>>(plan->shape, plan->axis_tab);
-    // the staged fill writes row_ptr on its way; otherwise (no entries, or rows too long for it) its own kernel does
-    bool have_row_ptr = false;
-    if (nnz > 0) have_row_ptr = launch_fill<true, TR>(plan, kernel_dev, idx_dev, vals_dev, q, ptr_dev);
-    if (!have_row_ptr)
-        row_ptr_kernel<TR><<<(unsigned)rp_blocks, kRowPtrThreads, 0, q>>>(plan->shape, plan->axis_tab, ptr_dev);
-    if (nnz > 0) {
-        for (int ch = 1; ch < channels; ++ch)      // the other channels share the indices: values only
-            launch_fill<false, TR>(plan, kernel_dev + (size_t)ch * k * k, nullptr, vals_dev + (size_t)ch * nnz, q);
-    }
-    if (!hip_ok(hipGetLastError())) {
+    const LaunchScope scope;
+    build_enqueue<TR>(plan, kernel_dev, ptr_dev, idx_dev, vals_dev, rp_blocks, (hipStream_t)stream);
+    if (!scope.ok()) {
         (void)hipFree(plan->axis_tab);
         delete plan;
         return CONV_EHIP;
@@ -258,6 +298,7 @@ int conv_compact_build_channels(int m, int n, int k, int s, int p, int channels,
     plan->transposed = false;
     plan->channels = channels;
     plan->compact = true;
+    plan->march_min_jobs = kMarchMinJobs;
     plan->desc = reinterpret_cast<const int2 *>(row_desc_dev);
     plan->ktab = ktab_dev;
     if (!hip_ok(hipGetDevice(&plan->device))) {
@@ -265,9 +306,10 @@ int conv_compact_build_channels(int m, int n, int k, int s, int p, int channels,
         return CONV_EHIP;
     }
     hipStream_t q = (hipStream_t)stream;
+    const LaunchScope scope;
     compact_rows_kernel<<<(unsigned)blocks, kCompactBuildThreads, 0, q>>>(plan->shape, reinterpret_cast<int2 *>(row_desc_dev));
     compact_table_kernel<<<(channels * k * k + 255) / 256, 256, 0, q>>>(kernel_dev, ktab_dev, channels * k * k);
-    if (!hip_ok(hipGetLastError())) {
+    if (!scope.ok()) {
         delete plan;
         return CONV_EHIP;
     }
@@ -277,10 +319,11 @@ int conv_compact_build_channels(int m, int n, int k, int s, int p, int channels,
 
 int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream) {
     if (!plan || !kernel_dev) return CONV_ENULL;
+    const LaunchScope scope;
     if (plan->compact) {
         const int kk = plan->shape.k * plan->shape.k * plan->channels;
         compact_table_kernel<<<(kk + 255) / 256, 256, 0, (hipStream_t)stream>>>(kernel_dev, plan->ktab, kk);
-        return hip_ok(hipGetLastError()) ? CONV_OK : CONV_EHIP;
+        return scope.ok() ? CONV_OK : CONV_EHIP;
     }
     if (plan->nnz == 0) return CONV_OK;
     const size_t kk = (size_t)plan->shape.k * plan->shape.k;
@@ -292,7 +335,7 @@ int conv_update_kernel(conv_plan *plan, const float *kernel_dev, void *stream) {
             launch_fill<false, false>(plan, kernel_dev + ch * kk, nullptr, plan->vals + (size_t)ch * plan->nnz,
                                       (hipStream_t)stream);
     }
-    if (!hip_ok(hipGetLastError())) return CONV_EHIP;
+    if (!scope.ok()) return CONV_EHIP;
     return CONV_OK;
 }
 
@@ -303,7 +346,7 @@ namespace {
 // ---------------------------------------------------------------------------
 // Apply dispatch
 // ---------------------------------------------------------------------------
-enum class Kind { GatherScalar, GatherVec, Tile, March };
+enum class Kind { GatherScalar, GatherVec, Tile, March, StageMarch };
 
 struct ApplyChoice {
     Kind kind;
@@ -314,8 +357,9 @@ struct ApplyChoice {
     int threads;
     size_t lds;
     TileGeom geom;
-    int ls;         // march kernel: output lines per step
-    int nl;         // march kernel: ring lines
+    int ls;         // march kernels: output lines per step
+    int nl;         // march kernels: ring lines
+    int xld;        // staged march: 16-byte loads per lane, array and pass
     MarchGeom march;
 };
 
@@ -382,9 +426,6 @@ bool tile_geometry(const conv_plan *plan, int batch, int tw, int plane, TileGeom
 // rows of up to 128 entries by 16 lanes (strips of 32 columns); the workgroup
 // is 512 threads either way.
 constexpr int kMarchThreads = 512;
-// Fewer strip segments than this cannot fill the chip; the row-group kernels
-// take such problems.  Adjustable through conv_set_march_min_jobs.
-std::atomic<int> g_march_min_jobs{256};
 
 struct MarchShape { int g, nit, tw; };
 bool march_shape(int max_row_nnz, MarchShape *out) {
@@ -442,7 +483,7 @@ bool march_geometry(const conv_plan *plan, int batch, int nv, int tw, MarchGeom 
     if (g.n_out < tw / 2) return false;                 // a strip would be mostly empty
     g.strips = (g.n_out + tw - 1) / tw;
     const int col_blocks = nv ? batch / (4 * nv) : batch;
-    if ((int64_t)g.strips * ((g.m_out + 7) / 8) * col_blocks < g_march_min_jobs.load(std::memory_order_relaxed)) return false;
+    if ((int64_t)g.strips * ((g.m_out + 7) / 8) * col_blocks < plan->march_min_jobs) return false;
     int64_t segs = kMarchTargetBlocks / ((int64_t)g.strips * col_blocks);
     if (segs < 1) segs = 1;
     int64_t seg = (g.m_out + segs - 1) / segs;
@@ -457,6 +498,78 @@ bool march_geometry(const conv_plan *plan, int batch, int nv, int tw, MarchGeom 
     *out = g;
     *ls_out = ls;
     *nl_out = nl;
+    return true;
+}
+
+// Marching kernel with the entry stream staged through LDS (apply_stage_march_kernel.h): strips of
+// 32 result columns, 8 waves, one workgroup per CU.  Lanes per row by the longest row, so that the
+// entries of a wave's 64 / G rows fit its LDS image; result lines per step WL = G (G = 2: 8 ...).
+constexpr int kStageNl = 16;
+constexpr int kStageTargetBlocks = 256;
+constexpr int kStageXld = 3;
+struct StageShape { int g, nit, nld; };
+bool stage_shape(int max_row_nnz, StageShape *out) {
+    // Rows of 3 x 3 taps: the fixed cost of a pass is not paid back (224^2, k 3, batch 256: 41 us
+    // against 37 us from the tile kernel).  Rows of more than 100 entries would need 8 lanes per
+    // row and two result lines per step; the other marching kernel, with 16 lanes per row, measured
+    // faster there (4096^2, k 11, s 4, batch 4: 246 us against 308 us).
+    if (max_row_nnz < 16) return false;
+    if (max_row_nnz <= 26) *out = StageShape{2, 13, 4};
+    else if (max_row_nnz <= 50) *out = StageShape{2, 25, 7};
+    else if (max_row_nnz <= 100) *out = StageShape{4, 25, 7};
+    else return false;
+    return true;
+}
+constexpr size_t stage_lds(int nv, int nld) {
+    return (nv ? (size_t)nv * stage_plane(nv, nld) * 16 : (size_t)stage_plane(0, nld) * 4) +
+           (size_t)kStageWaves * stage_wave_bytes(nld);
+}
+
+bool stage_march_geometry(const conv_plan *plan, int batch, int nv, const StageShape &ss, MarchGeom *out, int *wl_out) {
+    const ConvShape &sh = plan->shape;
+    const bool tr = plan->transposed;
+    MarchGeom g{};
+    g.m = tr ? sh.m_out : sh.m;
+    g.n = tr ? sh.n_out : sh.n;
+    g.m_out = tr ? sh.m : sh.m_out;
+    g.n_out = tr ? sh.n : sh.n_out;
+    g.s = sh.s; g.p = sh.p; g.k = sh.k;
+    g.tr = tr ? 1 : 0;
+    g.batch = batch;
+    g.nnz = (int)plan->nnz;
+    g.max_row = plan->max_row_nnz;
+    const int tw = kStageTw, rw = kWave / ss.g, wl = kStageWaves / (tw / rw);
+    // the image must hold the rows of a wave: (rw - 1) full rows, the slots of the last one, 3 entries of alignment
+    if ((int64_t)(rw - 1) * plan->max_row_nnz + (int64_t)ss.nit * ss.g + 3 > (int64_t)ss.nld * 256) return false;
+    // operand columns a strip can touch, operand lines WL result lines can touch, new lines per step -- upper bounds
+    const int64_t iw = tr ? (int64_t)(tw - 2 + sh.k) / sh.s + 2 : (int64_t)(tw - 1) * sh.s + sh.k;
+    const int64_t need = tr ? (int64_t)(wl - 2 + sh.k) / sh.s + 2 : (int64_t)sh.s * (wl - 1) + sh.k;
+    const int64_t fresh = tr ? (int64_t)wl / sh.s + 1 : (int64_t)sh.s * wl;
+    const int plane = stage_plane(nv, ss.nld), planes = nv ? nv : 1;
+    if (need > kStageNl || iw + 16 > plane) return false;
+    g.iw = (int)iw;
+    g.iw_pitch = round_up_mod((int)iw, 16, 8);
+    if ((int64_t)kStageNl * g.iw_pitch + 1 > plane) return false;
+    if (fresh * iw * planes > (int64_t)kStageXld * kWave * kStageWaves) return false;     // line registers per thread
+    // int arithmetic in the kernel, as for the other marching kernel
+    if ((int64_t)sh.m + 2LL * sh.p + sh.k >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + iw >= (1LL << 30)) return false;
+    if ((int64_t)g.m * g.n > (1LL << 27) || 2LL * kStageNl * g.n * 16 > (1LL << 25)) return false;
+    if (g.n_out < tw / 2) return false;                 // a strip would be mostly empty
+    g.strips = (g.n_out + tw - 1) / tw;
+    const int col_blocks = nv ? batch / (4 * nv) : batch;
+    if ((int64_t)((g.n_out + 63) / 64) * ((g.m_out + 7) / 8) * col_blocks < plan->march_min_jobs) return false;   // jobs of 64 columns x 8 lines, as for the other kernel
+    int64_t segs = kStageTargetBlocks / ((int64_t)g.strips * col_blocks);
+    if (segs < 1) segs = 1;
+    int64_t seg = (g.m_out + segs - 1) / segs;
+    seg = (seg + wl - 1) / wl * wl;
+    g.seg = (int)seg;
+    g.segs = (int)((g.m_out + seg - 1) / seg);
+    const int64_t jobs = (int64_t)g.strips * g.segs;
+    if (jobs + kXcds >= (1LL << 31) / kXcds) return false;
+    g.blocks_per_xcd = (int)((jobs + kXcds - 1) / kXcds);
+    g.inv_n = 1.0f / (float)g.n;
+    *out = g;
+    *wl_out = wl;
     return true;
 }
 
@@ -481,6 +594,21 @@ ApplyChoice choose_apply(const conv_plan *full, const float *x, const float *y, 
     MarchShape ms;
     MarchGeom mg;
     int ls, nl;
+    StageShape ss;
+    int wl;
+    if (stage_shape(plan->max_row_nnz, &ss) && stage_march_geometry(plan, batch, c.nv, ss, &mg, &wl)) {
+        c.kind = Kind::StageMarch;
+        c.g = ss.g;
+        c.nit = ss.nit;
+        c.tw = kStageTw;
+        c.threads = kStageWaves * kWave;
+        c.lds = stage_lds(c.nv, ss.nld);
+        c.ls = wl;
+        c.nl = kStageNl;
+        c.xld = ss.nld;          // (16-byte loads per lane, array and pass)
+        c.march = mg;
+        return c;
+    }
     if (march_shape(plan->max_row_nnz, &ms) && march_geometry(plan, batch, c.nv, ms.tw, &mg, &ls, &nl)) {
         c.kind = Kind::March;
         c.g = ms.g;
@@ -606,7 +734,7 @@ bool launch_march_inst(const ApplyChoice &c, const conv_plan *plan, const float 
     static thread_local bool allowed[64];
     if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
     MarchGeom g = c.march;
-    g.col_blocks = NV ? g.batch / (4 * NV) : g.batch;
+    g.col_blocks = g.batch / (NV ? 4 * NV : 1);
     const int64_t blocks = (int64_t)g.blocks_per_xcd * kXcds * g.col_blocks;
     if (blocks > kInt32Limit) return false;
     kern<<<dim3((unsigned)blocks), c.threads, c.lds, q>>>(plan->row_ptr, plan->col_idx, plan->vals, x, y, g);
@@ -639,6 +767,37 @@ bool launch_march(const ApplyChoice &c, const conv_plan *plan, const float *x, f
         case 1: return launch_march_nv<1>(c, plan, x, y, q);
         case 2: return launch_march_nv<2>(c, plan, x, y, q);
         default: return launch_march_nv<4>(c, plan, x, y, q);
+    }
+}
+
+template <int G, int NIT, int NLD, int NV>
+bool launch_stage_march_inst(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    auto kern = spmm_stage_march_kernel<G, NIT, NV, kStageNl, kStageXld, NLD, stage_plane(NV, NLD)>;
+    static thread_local bool allowed[64];
+    if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
+    MarchGeom g = c.march;
+    g.col_blocks = g.batch / (NV ? 4 * NV : 1);
+    const int64_t blocks = (int64_t)g.blocks_per_xcd * kXcds * g.col_blocks;
+    if (blocks > kInt32Limit) return false;
+    kern<<<dim3((unsigned)blocks), c.threads, c.lds, q>>>(plan->row_ptr, plan->col_idx, plan->vals, x, y, g);
+    return true;
+}
+
+template <int NV>
+bool launch_stage_march_nv(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    if (c.g == 2) {
+        if (c.nit == 13) return launch_stage_march_inst<2, 13, 4, NV>(c, plan, x, y, q);
+        return launch_stage_march_inst<2, 25, 7, NV>(c, plan, x, y, q);
+    }
+    return launch_stage_march_inst<4, 25, 7, NV>(c, plan, x, y, q);
+}
+
+bool launch_stage_march(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    switch (c.nv) {
+        case 0: return launch_stage_march_nv<0>(c, plan, x, y, q);
+        case 1: return launch_stage_march_nv<1>(c, plan, x, y, q);
+        case 2: return launch_stage_march_nv<2>(c, plan, x, y, q);
+        default: return launch_stage_march_nv<4>(c, plan, x, y, q);
     }
 }
 
@@ -916,19 +1075,20 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
         if (xb < ye && yb < xe) return CONV_EALIAS;
     }
     hipStream_t q = (hipStream_t)stream;
+    const LaunchScope scope;
     if (plan->compact) {
         const ChannelsChoice fused = choose_compact_channels(plan, x_dev, y_dev, batch);
         if (fused.ok) {
             launch_compact_channels(fused, plan, x_dev, y_dev, q);
-            return hip_ok(hipGetLastError()) ? CONV_OK : CONV_EHIP;
+            return scope.ok() ? CONV_OK : CONV_EHIP;
         }
         const CompactChoice cc = choose_compact(plan, x_dev, y_dev, batch);
         if (!cc.ok) return CONV_EOVERFLOW;
         if (!launch_compact(cc, plan, x_dev, y_dev, q)) return CONV_EHIP;
-        return hip_ok(hipGetLastError()) ? CONV_OK : CONV_EHIP;
+        return scope.ok() ? CONV_OK : CONV_EHIP;
     }
     const ApplyChoice c = choose_apply(plan, x_dev, y_dev, batch);
-    if (c.kind == Kind::March || c.kind == Kind::Tile) {
+    if (c.kind == Kind::March || c.kind == Kind::Tile || c.kind == Kind::StageMarch) {
         // one launch per channel: the first stores y, the others add to it
         conv_plan one = *plan;
         one.cols = plan->cols / plan->channels;
@@ -938,8 +1098,9 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
             one.vals = plan->vals + (size_t)ch * plan->nnz;
             const float *x_ch = x_dev + (size_t)ch * one.cols * batch;
             cc.march.accum = cc.geom.accum = ch > 0;
-            const bool ok = c.kind == Kind::March ? launch_march(cc, &one, x_ch, y_dev, q)
-                                                  : launch_tile(cc, &one, x_ch, y_dev, q);
+            const bool ok = c.kind == Kind::StageMarch ? launch_stage_march(cc, &one, x_ch, y_dev, q)
+                            : c.kind == Kind::March   ? launch_march(cc, &one, x_ch, y_dev, q)
+                                                      : launch_tile(cc, &one, x_ch, y_dev, q);
             if (!ok) return CONV_EHIP;
         }
     } else {
@@ -951,7 +1112,7 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
             default: launch_gather<16>(c, plan, x_dev, y_dev, batch, q); break;
         }
     }
-    if (!hip_ok(hipGetLastError())) return CONV_EHIP;
+    if (!scope.ok()) return CONV_EHIP;
     return CONV_OK;
 }
 
@@ -1056,6 +1217,7 @@ int conv_spmv_from_csc(const conv_plan *plan, const float *x_dev, float *y_dev, 
         if (xb < ye && yb < xe) return CONV_EALIAS;
     }
     hipStream_t q = (hipStream_t)stream;
+    const LaunchScope scope;
     const long long count = (long long)out_pixels * batch;
     const unsigned fill_blocks = (unsigned)std::min<long long>((count / 4 + kGatherThreads) / kGatherThreads, 1 << 16);
     fill_zero_kernel<<<fill_blocks, kGatherThreads, 0, q>>>(y_dev, count);
@@ -1093,7 +1255,7 @@ int conv_spmv_from_csc(const conv_plan *plan, const float *x_dev, float *y_dev, 
 #undef CONV_SCATTER_BL
 #undef CONV_SCATTER
     }
-    return hip_ok(hipGetLastError()) ? CONV_OK : CONV_EHIP;
+    return scope.ok() ? CONV_OK : CONV_EHIP;
 }
 
 // ---------------------------------------------------------------------------
@@ -1166,9 +1328,10 @@ int conv_multi_apply(const conv_multi *multi, void *stream) {
     if (!multi) return CONV_ENULL;
     if (multi->blocks == 0) return CONV_OK;
     const unsigned by = (unsigned)(multi->batch > 65535 ? 65535 : multi->batch);
+    const LaunchScope scope;
     spmm_multi_kernel<<<dim3(multi->blocks, by), kGatherThreads, 0, (hipStream_t)stream>>>(multi->descs_dev, multi->n,
                                                                                             multi->batch);
-    if (!hip_ok(hipGetLastError())) return CONV_EHIP;
+    if (!scope.ok()) return CONV_EHIP;
     return CONV_OK;
 }
 
@@ -1203,7 +1366,13 @@ int conv_plan_is_compact(const conv_plan *plan) { return plan ? (plan->compact ?
 int conv_plan_channels(const conv_plan *plan) { return plan ? plan->channels : CONV_ENULL; }
 
 int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage, int channels, conv_dispatch *out) {
+    return conv_test_dispatch_info(m, n, k, s, p, batch, storage, channels, kMarchMinJobs, out);
+}
+
+int conv_test_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage, int channels,
+                            int march_min_jobs, conv_dispatch *out) {
     if (!out) return CONV_ENULL;
+    if (march_min_jobs < 1) return CONV_EINVAL;
     int64_t mo, no;
     const int st = check_shape(m, n, k, s, p, &mo, &no);
     if (st != CONV_OK) return st;
@@ -1225,6 +1394,7 @@ int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage
     plan.nnz = nnz;
     const int per_axis = plan.transposed ? (k + s - 1) / s : k;
     plan.max_row_nnz = per_axis * per_axis;
+    plan.march_min_jobs = march_min_jobs;
     conv_dispatch d{};
     const ChannelsChoice fused = choose_compact_channels(&plan, nullptr, nullptr, batch);
     if (storage == 3) {
@@ -1275,12 +1445,21 @@ int conv_dispatch_info(int m, int n, int k, int s, int p, int batch, int storage
         d.workgroups = (int64_t)cc.geom.strips * cc.geom.segs * cc.col_blocks;
     } else {
         const ApplyChoice c = choose_apply(&plan, nullptr, nullptr, batch);
-        d.kernel = c.kind == Kind::GatherScalar ? 0 : c.kind == Kind::GatherVec ? 1 : c.kind == Kind::Tile ? 2 : 3;
+        d.kernel = c.kind == Kind::GatherScalar ? 0 : c.kind == Kind::GatherVec ? 1 : c.kind == Kind::Tile ? 2
+                   : c.kind == Kind::March ? 3 : 9;
         d.threads = c.threads;
         d.lds_bytes = (int64_t)c.lds;
         d.lanes_per_row = c.g;
         d.columns_per_lane = c.nv ? 4 * c.nv : 1;
-        if (c.kind == Kind::March) {
+        if (c.kind == Kind::StageMarch) {
+            const bool tr = plan.transposed;
+            d.strip = c.tw;
+            d.segment = c.march.seg;
+            d.ring_lines = c.nl;
+            d.lines_per_step = c.ls;
+            d.ring_lines_needed = tr ? (c.ls - 2 + k) / s + 2 : s * (c.ls - 1) + k;
+            d.workgroups = (int64_t)c.march.strips * c.march.segs * (c.nv ? batch / (4 * c.nv) : batch);
+        } else if (c.kind == Kind::March) {
             const bool tr = plan.transposed;
             d.strip = c.tw;
             d.segment = c.march.seg;
@@ -1333,13 +1512,19 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch) {
             else
                 snprintf(name, sizeof name, "lds_march_%dx%d_ring%d_step%d_g%d_nit%d_scalar", c.march.seg, c.tw, c.nl, c.ls, c.g, c.nit);
             break;
+        case Kind::StageMarch:
+            if (c.nv)
+                snprintf(name, sizeof name, "lds_march_staged_%dx%d_ring%d_step%d_g%d_nit%d_float4x%d", c.march.seg, c.tw, c.nl, c.ls, c.g, c.nit, c.nv);
+            else
+                snprintf(name, sizeof name, "lds_march_staged_%dx%d_ring%d_step%d_g%d_nit%d_scalar", c.march.seg, c.tw, c.nl, c.ls, c.g, c.nit);
+            break;
         case Kind::Tile:
             snprintf(name, sizeof name, "lds_tile_%dx%d_g%d_nit%d_float4x%d", c.geom.th, c.tw, c.g, c.nit, c.nv);
             break;
     }
     if (plan->channels > 1) {
         const size_t len = strlen(name);
-        const bool per_channel = c.kind == Kind::March || c.kind == Kind::Tile;
+        const bool per_channel = c.kind == Kind::March || c.kind == Kind::Tile || c.kind == Kind::StageMarch;
         snprintf(name + len, sizeof name - len, per_channel ? "_x%d_launches" : "_%d_channels", plan->channels);
     }
     return name;
@@ -1374,9 +1559,12 @@ const char *conv_strerror(int status) {
 
 int conv_last_hip_error(void) { return g_last_hip_error; }
 
-int conv_set_march_min_jobs(int jobs) {
+int conv_plan_set_march_min_jobs(conv_plan *plan, int jobs) {
+    if (!plan) return CONV_ENULL;
     if (jobs < 1) return CONV_EINVAL;
-    return g_march_min_jobs.exchange(jobs);
+    const int prev = plan->march_min_jobs;
+    plan->march_min_jobs = jobs;
+    return prev;
 }
 
 }  // extern "C"

@@ -95,3 +95,35 @@ def densenet121_sweep(batch: int = 1, seed: int = 121):
         x = rng.standard_normal(m * n * batch, dtype=np.float32)
         K = rng.standard_normal(k * k, dtype=np.float32)
         yield (m, n, k, s, p), x, K
+
+
+def march_edge_grid(transposed: bool = False, every: int = 3):
+    """Small shapes at the edge of what the strip-marching apply kernels accept, as
+    ((m, n, k, s, p), batch) pairs: one to a few result lines, strips with ragged ends, every
+    padding from none to beyond the kernel (empty rows, k > m, slide remainders).  Result lines
+    must hold at least 32 pixels and rows at least 16 entries (k >= 4 for T; ceil(k/s) >= 4 for
+    the transposed matrix, whose result lines are the input lines).  Every `every`-th shape of
+    the full product is kept (the stride is coprime to the loop lengths), batches 1, 4, 8, 16
+    in turn."""
+    ms = (1, 2, 3, 9, 17, 33)
+    ns = tuple(range(30, 41)) + tuple(range(63, 67)) + tuple(range(127, 131))
+    ks = (4, 5, 7, 9, 11)
+    batches = (1, 4, 8, 16)
+    idx = kept = 0
+    for m in ms:
+        for n in ns:
+            for k in ks:
+                for s in (1, 2, 3):
+                    for p in range(0, k + 2):
+                        if k > m + 2 * p or k > n + 2 * p:
+                            continue
+                        if transposed:
+                            if n < 32 or -(-k // s) < 4:
+                                continue
+                        elif (n + 2 * p - k) // s + 1 < 32:
+                            continue
+                        idx += 1
+                        if idx % every:
+                            continue
+                        yield (m, n, k, s, p), batches[kept % 4]
+                        kept += 1

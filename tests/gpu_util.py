@@ -14,9 +14,21 @@ def device():
     return torch.device("cuda:0")
 
 
+# Test hook: when set, every plan built through this module gets this threshold for the
+# persistent marching kernels (the default, 256 strip segments, keeps them off small shapes).
+MARCH_MIN_JOBS = None
+
+
+def _hooked(plan):
+    if MARCH_MIN_JOBS is not None:
+        cs.conv_plan_set_march_min_jobs(plan, MARCH_MIN_JOBS)
+    return plan
+
+
 def build_plan(shape, K):
     m, n, k, s, p = shape
-    return cs.conv_csr_build(m, n, k, s, p, torch.from_numpy(np.ascontiguousarray(K, dtype=np.float32)).to(device()))
+    return _hooked(cs.conv_csr_build(m, n, k, s, p,
+                                     torch.from_numpy(np.ascontiguousarray(K, dtype=np.float32)).to(device())))
 
 
 def check_csr(plan, shape, K):
@@ -58,7 +70,8 @@ def check_apply(plan, shape, K, x, batch, x_dev=None):
 
 def build_plan_t(shape, K):
     m, n, k, s, p = shape
-    return cs.conv_csc_build(m, n, k, s, p, torch.from_numpy(np.ascontiguousarray(K, dtype=np.float32)).to(device()))
+    return _hooked(cs.conv_csc_build(m, n, k, s, p,
+                                     torch.from_numpy(np.ascontiguousarray(K, dtype=np.float32)).to(device())))
 
 
 def check_csc(plan, shape, K):

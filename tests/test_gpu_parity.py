@@ -200,26 +200,32 @@ def test_errors_on_device_calls():
 
 @pytest.fixture
 def march_everywhere():
-    prev = cs.conv_set_march_min_jobs(1)
+    import gpu_util
+    gpu_util.MARCH_MIN_JOBS = 1
     yield
-    cs.conv_set_march_min_jobs(prev)
+    gpu_util.MARCH_MIN_JOBS = None
 
 
-def test_march_exhaustive_tiny_grid(march_everywhere):
-    batches = itertools.cycle([1, 4, 8, 16])
+def test_march_edge_grid(march_everywhere):
+    """The smallest shapes the marching kernels accept (workloads.march_edge_grid: one to a few
+    output lines, strips with ragged ends, every padding from none to beyond the kernel, so
+    empty rows, k > m and slide remainders all occur), each against the sliding-window oracle.
+    Four in five of them must really take a marching kernel (all of those with stride 1; the
+    CPU test test_march_edge_grid_dispatch checks which ones do not)."""
     count = used = 0
-    for shape in itertools.product(range(1, 6), range(1, 6), range(1, 5), range(1, 4), range(0, 5)):
-        m, n, k, s, p = shape
-        if k > m + 2 * p or k > n + 2 * p:
-            continue
-        batch = next(batches)
+    kinds = set()
+    for shape, batch in workloads.march_edge_grid():
         x, K = _rand(shape, batch, 1000 + count)
         plan = build_plan(shape, K)
-        used += plan.variant(batch).startswith("lds_march")
+        variant = plan.variant(batch)
+        if variant.startswith("lds_march"):
+            used += 1
+            kinds.add("staged" if variant.startswith("lds_march_staged") else "groups")
         check_apply(plan, shape, K, x, batch)
         plan.close()
         count += 1
-    assert count > 1000
+    assert count > 1500 and used >= 0.8 * count, (count, used)
+    assert kinds == {"staged", "groups"}
 
 
 MARCH_CASES = [

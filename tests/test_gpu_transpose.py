@@ -147,25 +147,25 @@ def test_transposed_update_kernel_and_fused_apply():
 
 @pytest.fixture
 def march_everywhere():
-    prev = cs.conv_set_march_min_jobs(1)
+    import gpu_util
+    gpu_util.MARCH_MIN_JOBS = 1
     yield
-    cs.conv_set_march_min_jobs(prev)
+    gpu_util.MARCH_MIN_JOBS = None
 
 
-def test_transposed_march_exhaustive_tiny_grid(march_everywhere):
-    batches = itertools.cycle([1, 4, 8, 16])
-    count = 0
-    for shape in itertools.product(range(1, 6), range(1, 6), range(1, 5), range(1, 4), range(0, 5)):
-        m, n, k, s, p = shape
-        if k > m + 2 * p or k > n + 2 * p:
-            continue
-        batch = next(batches)
+def test_transposed_march_edge_grid(march_everywhere):
+    """z = T^T u on the smallest shapes the marching kernels accept for the transposed matrix
+    (workloads.march_edge_grid(transposed=True): result lines are input lines here, so n >= 32
+    and ceil(k/s)^2 >= 9 entries per row), each against the scatter-and-crop oracle."""
+    count = used = 0
+    for shape, batch in workloads.march_edge_grid(transposed=True):
         u, K = _rand_t(shape, batch, 2000 + count)
         plan = build_plan_t(shape, K)
+        used += plan.variant(batch).startswith("lds_march")
         check_apply_t(plan, shape, K, u, batch)
         plan.close()
         count += 1
-    assert count > 1000
+    assert count > 1000 and used >= 0.8 * count, (count, used)
 
 
 def test_transposed_march_ragged_shapes(march_everywhere):

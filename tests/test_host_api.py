@@ -106,7 +106,9 @@ def test_argument_validation_without_a_gpu():
     assert lib.conv_multi_create(1, arr, arr, arr, 1, ctypes.byref(m_out)) == -2 and m_out.value is None
     assert lib.conv_multi_apply(None, None) == -2
     assert lib.conv_multi_destroy(None) == 0
-    assert lib.conv_set_march_min_jobs(0) == -1
+    assert lib.conv_plan_set_march_min_jobs(None, 4) == -2
+    d = binding.ConvDispatch()
+    assert lib.conv_test_dispatch_info(64, 64, 3, 1, 1, 1, 0, 1, 0, ctypes.byref(d)) == -1       # threshold < 1
 
 
 def test_strerror_texts():
@@ -205,6 +207,12 @@ def test_dispatch_geometry_is_consistent_over_many_shapes():
                     rows = k * k if storage == 0 else ((k + s - 1) // s) ** 2
                     assert 16 <= rows <= 128 and d["strip"] in (32, 64) and d["segment"] % 2 == 0
                     assert d["lines_per_step"] in (1, 2) and d["threads"] == 512
+                if d["kernel"] == 9:        # entries staged through LDS: rows of 16 to 100 entries, 2 or 4 lanes per row
+                    rows = k * k if storage == 0 else ((k + s - 1) // s) ** 2
+                    assert 16 <= rows <= 100 and d["strip"] == 32 and d["lanes_per_row"] in (2, 4)
+                    assert d["lanes_per_row"] == (2 if rows <= 50 else 4)
+                    assert d["lines_per_step"] * d["lanes_per_row"] == 16 and d["threads"] == 512
+                    assert d["segment"] % d["lines_per_step"] == 0 and d["ring_lines"] == 16
                 if d["kernel"] == 5:        # rectangle path: only the compiled (k, s)
                     assert (s == 1 and k in (1, 3, 5, 7, 9)) or (s == 2 and k in (2, 3, 5, 7))
                     assert d["lines_per_step"] == (4 if s == 1 else 2) and d["strip"] * d["lanes_per_row"] == 256
@@ -216,10 +224,66 @@ def test_dispatch_geometry_is_consistent_over_many_shapes():
                 if storage == 2:
                     assert d["kernel"] in (4, 5)
                 else:
-                    assert d["kernel"] in (0, 1, 2, 3)
+                    assert d["kernel"] in (0, 1, 2, 3, 9)
                     if batch % 4:
                         assert d["columns_per_lane"] == 1
-    assert seen == {0, 1, 2, 3, 4, 5}
+    assert seen == {0, 1, 2, 3, 4, 5, 9}
+
+
+def test_march_edge_grid_dispatch():
+    """The shapes of the GPU tests' edge grids, with the test hook's threshold of one job, go to a
+    marching kernel (3: entries loaded by the lane groups, 9: entries staged through LDS) -- except where the geometry
+    refuses, and it refuses only at strides above 1 (or rows of fewer than 16 entries): every shape
+    of the grids with stride 1 marches, and four in five overall."""
+    for transposed in (False, True):
+        total = marching = 0
+        kinds = set()
+        for (m, n, k, s, p), batch in workloads.march_edge_grid(transposed=transposed):
+            d = cs.conv_dispatch_info(m, n, k, s, p, batch, 1 if transposed else 0, 1, march_min_jobs=1)
+            total += 1
+            if d.kernel in (3, 9):
+                marching += 1
+                kinds.add(d.kernel)
+                assert d.ring_lines_needed <= d.ring_lines and d.lds_bytes <= 160 * 1024
+            else:
+                # refusals: only at strides above 1, where a step adds more operand lines than the
+                # kernels' line registers hold or the ring is too short, or rows are too short
+                rows = ((k + s - 1) // s) ** 2 if transposed else k * k
+                assert s > 1 or rows < 16, ((m, n, k, s, p), batch, d.kernel)
+        assert total > 1500 and marching >= 0.8 * total, (transposed, total, marching)
+        assert kinds == {3, 9}
+    # with the default threshold none of these small shapes marches
+    for (m, n, k, s, p), batch in list(workloads.march_edge_grid())[::50]:
+        assert cs.conv_dispatch_info(m, n, k, s, p, batch).kernel in (0, 1, 2)
+
+
+def test_march_quotient_trick_is_exact():
+    """The marching kernels locate a stored column in the LDS ring by di = trunc(fma(float(dB),
+    inv_nB, 0.5/n)) with dB = PIXB*(di*n + dj) a multiple of PIXB below 2^25, inv_nB the rounded
+    1/(n*PIXB): the quotient must come out exact for every dj in [0, n) and every line di the
+    ring can hold (di < 2*NL = 32), for all n the host guard lets through (2*NL*n*16 <= 2^25,
+    n <= 65536), for 16- and 4-byte pixels."""
+    rng = np.random.default_rng(7)
+    ns = sorted(set([1, 2, 3, 5, 7, 30, 31, 32, 33, 63, 64, 65, 224, 1000, 1023, 1024, 1025, 4096, 4099, 6600, 16384,
+                     32767, 32768, 32769, 65535, 65536] + [int(v) for v in rng.integers(1, 65537, size=60)]))
+    for pixb in (16, 4):
+        for n in ns:
+            inv_n = np.float32(1.0) / np.float32(n)
+            inv_nb = inv_n / np.float32(pixb)
+            half = np.float32(0.5) * inv_n
+            # every line, and per line the first, last and a sample of the pixels (all of them for small n)
+            dj = np.arange(n, dtype=np.int64) if n <= 4096 else np.unique(np.concatenate(
+                [np.arange(0, 64), np.arange(n - 64, n), rng.integers(0, n, size=2000)]))
+            di = np.arange(32, dtype=np.int64)[:, None]
+            db = (di * n + dj[None, :]) * pixb
+            assert db.max() < 2 ** 25 * (pixb // 4 if pixb == 4 else 1) or n > 65536 // 2
+            f = db.astype(np.float32)                       # exact: below 2^25 and a multiple of pixb >= 4, or below 2^24
+            assert np.array_equal(f.astype(np.int64), db)
+            # one fused multiply-add, rounded once: evaluate in float64 (exact product of two floats plus
+            # a float is within float64's reach here) and round to float32
+            q = (f.astype(np.float64) * np.float64(inv_nb) + np.float64(half)).astype(np.float32)
+            got = q.astype(np.int64)
+            assert np.array_equal(got, np.broadcast_to(di, got.shape)), (pixb, n)
 
 
 def test_dispatch_of_channel_sums_from_the_structure_aware_storage():
@@ -299,19 +363,19 @@ def test_dispatch_of_the_product_from_csc_over_many_shapes():
 
 
 def test_dispatch_of_the_named_workloads():
-    want = {"small_32_k3": 0, "strided_256_k5_b64": 2, "headline_1024_k7_b1": 3, "headline_1024_k7_b16": 3,
+    want = {"small_32_k3": 0, "strided_256_k5_b64": 2, "headline_1024_k7_b1": 9, "headline_1024_k7_b16": 9,
             "cnn_224_k3_b256": 2, "padheavy_512_k9_s3": 0, "padheavy_4096_k11_s4_b4": 3}
     for name, kernel in want.items():
         w = workloads.WORKLOADS[name]
         assert _dispatch(*w.shape, w.batch)["kernel"] == kernel, name
     d = _dispatch(*workloads.WORKLOADS["headline_1024_k7_b16"].shape, 16)
     assert (d["strip"], d["segment"], d["ring_lines"], d["lines_per_step"], d["lds_bytes"], d["workgroups"]) == \
-        (64, 32, 16, 2, 73984, 512)
+        (32, 128, 16, 8, 163072, 256)
     c = _dispatch(*workloads.WORKLOADS["headline_1024_k7_b16"].shape, 16, storage=2)
     assert (c["kernel"], c["strip"], c["segment"], c["lines_per_step"], c["workgroups"]) == (5, 64, 32, 4, 512)
     # several channels: the LDS tile kernel is not used (one launch per channel would not pay)
     assert _dispatch(224, 224, 3, 1, 1, 16, 0, 64)["kernel"] == 1
-    assert _dispatch(1024, 1024, 7, 1, 3, 16, 0, 3)["kernel"] == 3
+    assert _dispatch(1024, 1024, 7, 1, 3, 16, 0, 3)["kernel"] == 9
     for bad in [(4, 4, 9, 1, 0, 1, 0, 1), (8, 8, 3, 1, 1, 0, 0, 1), (8, 8, 3, 1, 1, 1, 4, 1), (8, 8, 3, 1, 1, 1, 1, 2),
                 (300, 300, 256, 1, 0, 1, 2, 1)]:
         with pytest.raises(cs.ConvError):
