@@ -67,7 +67,8 @@ int64_t conv_nnz(int m, int n, int k, int s, int p);
  * they must outlive it and must not be modified while an apply is in flight.
  * The plan itself owns a small device table (the two per-axis prefix sums of
  * the row-length factors, (m_out + n_out + 2) int32), allocated here with
- * hipMalloc and released by conv_plan_destroy (both synchronise the device).
+ * hipMalloc and released by conv_plan_destroy (both synchronise the device; a
+ * caller that must not allocate uses conv_csr_fill_noalloc).
  * Argument errors (CONV_EINVAL, CONV_ENULL, CONV_EOVERFLOW, CONV_ENOMEM) are
  * found before anything is enqueued.  CONV_EHIP means that one of this call's
  * own launches failed: earlier launches of the call may already be enqueued.
@@ -77,6 +78,21 @@ int conv_csr_build(int m, int n, int k, int s, int p,
                    const float *kernel_dev,
                    int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev,
                    void *stream, conv_plan **plan_out);
+
+/* For callers that cannot allocate (code under HIP graph capture, serving loops,
+ * harnesses that forbid hipMalloc): the three CSR arrays of conv_csr_build,
+ * written by the same kernels, with no allocation of any kind -- no plan object
+ * is made and the per-axis prefix tables live in a device array inside this
+ * library (256 KiB per device, held until the process ends) instead of a table
+ * owned by a plan.  Arguments as for conv_csr_build.  Limits: m_out + n_out + 2
+ * <= 65536 (CONV_EOVERFLOW beyond).  Every call on one device uses that device's
+ * one array: calls whose kernels may overlap on the same device (different
+ * streams) race on it and must be ordered by the caller; calls on one stream
+ * are safe.  The device that is current at the call is used. */
+int conv_csr_fill_noalloc(int m, int n, int k, int s, int p,
+                          const float *kernel_dev,
+                          int32_t *row_ptr_dev, int32_t *col_idx_dev, float *vals_dev,
+                          void *stream);
 
 /* Several input channels, one output (the multi-channel context the paper
  * names as an outlook, Section 4.2): y = sum over ch of T_ch x_ch, i.e. the

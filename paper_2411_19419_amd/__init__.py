@@ -16,6 +16,7 @@ from .binding import (  # noqa: F401
     conv_nnz,
     conv_out_shape,
     conv_plan_set_march_min_jobs,
+    conv_csr_fill_noalloc,
     conv_spmv,
     conv_spmv_from_csc,
     conv_strerror,

@@ -19,7 +19,7 @@ _lib = None
 EXPORTS = (
     "conv_out_shape", "conv_nnz", "conv_csr_build", "conv_spmv", "conv_plan_shape",
     "conv_spmv_variant", "conv_plan_destroy", "conv_strerror", "conv_last_hip_error",
-    "conv_plan_set_march_min_jobs", "conv_test_dispatch_info", "conv_update_kernel",
+    "conv_plan_set_march_min_jobs", "conv_test_dispatch_info", "conv_update_kernel", "conv_csr_fill_noalloc",
     "conv_multi_create", "conv_multi_apply", "conv_multi_destroy",
     "conv_csc_build", "conv_plan_is_transposed",
     "conv_compact_build", "conv_plan_is_compact",
@@ -108,6 +108,8 @@ def _load():
         lib.conv_plan_set_march_min_jobs.restype = i
         lib.conv_test_dispatch_info.argtypes = [i] * 9 + [ctypes.POINTER(ConvDispatch)]
         lib.conv_test_dispatch_info.restype = i
+        lib.conv_csr_fill_noalloc.argtypes = [i, i, i, i, i, vp, vp, vp, vp, vp]
+        lib.conv_csr_fill_noalloc.restype = i
         _lib = lib
         return lib
 
@@ -252,6 +254,25 @@ def conv_csr_build(m, n, k, s, p, kernel, stream=None, _transposed=False) -> Con
         raise ConvError(st, "%s%r" % ("conv_csc_build" if _transposed else "conv_csr_build", (m, n, k, s, p)))
     _on_stream(stream, row_ptr, col_idx, vals)
     return ConvPlan(handle, (m, n, k, s, p), (mo, no), nnz, row_ptr, col_idx, vals, kernel, transposed=_transposed)
+
+
+def conv_csr_fill_noalloc(m, n, k, s, p, kernel, row_ptr, col_idx, vals, stream=None) -> None:
+    """The three CSR arrays of conv_csr_build written into caller-provided tensors, with no
+    allocation by the library and no plan (see include/convspmv.h)."""
+    import torch
+    for t, dt in ((kernel, torch.float32), (row_ptr, torch.int32), (col_idx, torch.int32), (vals, torch.float32)):
+        if not (t.is_cuda and t.dtype == dt and t.is_contiguous()):
+            raise ValueError("operands must be contiguous device tensors of the documented types")
+    mo, no = conv_out_shape(m, n, k, s, p)
+    nnz = conv_nnz(m, n, k, s, p)
+    if kernel.numel() != k * k or row_ptr.numel() != mo * no + 1 or col_idx.numel() < nnz or vals.numel() < nnz:
+        raise ValueError("operand sizes do not match the shape")
+    with torch.cuda.device(kernel.device):
+        sh, _ = _stream_handle(stream)
+        st = _load().conv_csr_fill_noalloc(m, n, k, s, p, kernel.data_ptr(), row_ptr.data_ptr(),
+                                           col_idx.data_ptr() if nnz else None, vals.data_ptr() if nnz else None, sh)
+    if st != 0:
+        raise ConvError(st, "conv_csr_fill_noalloc%r" % ((m, n, k, s, p),))
 
 
 def conv_csr_build_channels(m, n, k, s, p, kernels, channels, stream=None) -> ConvPlan:

@@ -239,7 +239,48 @@ int build_impl(int m, int n, int k, int s, int p, int channels, const float *ker
 
 }  // namespace
 
+// ---------------------------------------------------------------------------
+// The CSR arrays without any allocation: the per-axis prefix tables live in a
+// device array of this library instead of a hipMalloc'ed table of the plan.
+// ---------------------------------------------------------------------------
+constexpr int kNoAllocAxisInts = 1 << 16;        // 256 KiB per device, held until the process ends
+static __device__ __align__(256) int scratch[kNoAllocAxisInts];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int *g_scratch_ptr[kMaxDevices];                 // device address of `scratch` on each device, once known
+
+// Device address of this device's copy of `scratch` (the array's name is a host-side stand-in
+// and must never be passed to a kernel).  Looked up once per device, with that device current.
+int *scratch_address(int device) {
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        int *ptr = nullptr;
+        if (!hip_ok(hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)))) return nullptr;
+        g_scratch_ptr[device] = ptr;
+    }
+    return g_scratch_ptr[device];
+}
+}  // namespace
+
 extern "C" {
+
+int conv_csr_fill_noalloc(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *row_ptr_dev,
+                          int32_t *col_idx_dev, float *vals_dev, void *stream) {
+    conv_plan plan;
+    int64_t rp_blocks = 0;
+    const int st = build_check<false>(m, n, k, s, p, 1, kernel_dev, row_ptr_dev, col_idx_dev, vals_dev, &plan, &rp_blocks);
+    if (st != CONV_OK) return st;
+    if ((int64_t)plan.shape.m_out + plan.shape.n_out + 2 > kNoAllocAxisInts) return CONV_EOVERFLOW;
+    if (!hip_ok(hipGetDevice(&plan.device))) return CONV_EHIP;
+    plan.axis_tab = scratch_address(plan.device);
+    if (!plan.axis_tab) return CONV_EHIP;
+    const LaunchScope scope;
+    build_enqueue<false>(&plan, kernel_dev, row_ptr_dev, col_idx_dev, vals_dev, rp_blocks, (hipStream_t)stream);
+    return scope.ok() ? CONV_OK : CONV_EHIP;
+}
 
 int conv_csr_build(int m, int n, int k, int s, int p, const float *kernel_dev, int32_t *row_ptr_dev,
                    int32_t *col_idx_dev, float *vals_dev, void *stream, conv_plan **plan_out) {

@@ -109,6 +109,12 @@ def test_argument_validation_without_a_gpu():
     assert lib.conv_plan_set_march_min_jobs(None, 4) == -2
     d = binding.ConvDispatch()
     assert lib.conv_test_dispatch_info(64, 64, 3, 1, 1, 1, 0, 1, 0, ctypes.byref(d)) == -1       # threshold < 1
+    # the entry point that allocates nothing checks its arguments like the build, and its size limit
+    assert lib.conv_csr_fill_noalloc(0, 4, 3, 1, 1, 16, 16, 16, 16, None) == -1
+    assert lib.conv_csr_fill_noalloc(8, 8, 3, 1, 1, None, 16, 16, 16, None) == -2
+    assert lib.conv_csr_fill_noalloc(8, 8, 3, 1, 1, 16, None, 16, 16, None) == -2
+    assert lib.conv_csr_fill_noalloc(40000, 40000, 3, 1, 1, 16, 16, 16, 16, None) == -3          # nnz beyond int32
+    assert lib.conv_csr_fill_noalloc(40000, 30000, 1, 1, 0, 16, 16, 16, 16, None) == -3          # m_out + n_out + 2 > 65536
 
 
 def test_strerror_texts():
