@@ -78,15 +78,18 @@ def cpu_model():
     return "unknown"
 
 
-def measured_traffic(variant):
+def launch_shape(cs, shape, batch, storage=0):
+    """Workgroups x threads and dynamic LDS bytes of the launch conv_spmv makes for this shape."""
+    d = cs.conv_dispatch_info(*shape, batch=batch, storage=storage)
+    return "%dx%d lds %d" % (d.workgroups, d.threads, d.lds_bytes)
+
+
+def measured_traffic(variant, launch):
     """HBM bytes per launch of the apply kernel from the committed rocprofv3 counter summary, or
-    None when there is none for this variant or the kernel sources have changed since."""
+    None when there is none for this variant and launch shape, or when the source files the
+    kernel is compiled from (the summary names them) have changed since the counters were taken."""
     import glob
     import hashlib
-    h = hashlib.sha256()
-    for fn in sorted(glob.glob(os.path.join(ROOT, "paper_2411_19419_amd", "csrc", "*"))):
-        with open(fn, "rb") as fh:
-            h.update(fh.read())
     for fn in glob.glob(os.path.join(ROOT, "profiles", "*.txt")):
         fields = {}
         with open(fn) as fh:
@@ -94,7 +97,16 @@ def measured_traffic(variant):
                 if ":" in line:
                     key, _, val = line.strip().partition(":")
                     fields[key.strip()] = val.strip()
-        if fields.get("traffic_kernel") == variant and fields.get("csrc_sha256") == h.hexdigest():
+        if fields.get("traffic_kernel") != variant or fields.get("traffic_launch") != launch:
+            continue
+        h = hashlib.sha256()
+        try:
+            for name in fields.get("traffic_sources", "").split():
+                with open(os.path.join(ROOT, "paper_2411_19419_amd", "csrc", name), "rb") as fh:
+                    h.update(fh.read())
+        except OSError:
+            continue
+        if fields.get("traffic_sources_sha256") == h.hexdigest():
             return int(fields["traffic_bytes_per_launch"])
     return None
 
@@ -431,6 +443,7 @@ def main():
     copy_bytes_each_way = src.numel() * 4
     del src, dst
 
+    launch = launch_shape(cs, w.shape, w.batch, storage=2 if args.compact else (1 if args.transposed else 0))
     gbs = model_bytes / (ms_per_step * 1e-3) / 1e9
     achieved = model_bytes / (region_avg * 1e-3) / 1e9
     out = {
@@ -461,8 +474,8 @@ def main():
         "value_over_copy": gbs / copy_gbs,
         "copy_bytes_each_way": copy_bytes_each_way,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(plan.variant(w.batch)),
-                     "kernel": plan.variant(w.batch), "kernel_ms_avg": region_avg,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(plan.variant(w.batch), launch),
+                     "kernel": plan.variant(w.batch), "launch": launch, "kernel_ms_avg": region_avg,
                      "timing": "two HIP events on the launch stream around the %d timed launches, elapsed / %d"
                                % (args.steps, args.steps),
                      "single_launch_ms_avg": kern_avg, "single_launch_ms_median": kern_ms[len(kern_ms) // 2],

@@ -142,22 +142,29 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
     // first row of the wave on line xo (clamped into the segment, so that every address is valid)
     auto wave_row = [&](int xo) { return (long long)min(xo, xb - 1) * g.n_out + y0 + min(wcol, twc - 1); };
     // first entry of the wave's span on line xo: a wave-uniform address, so a scalar load
-    auto span_begin = [&](int xo) { return __builtin_amdgcn_readfirstlane(row_ptr[wave_row(xo)]); };
+    // ... and one past its last entry (the end of the last row the wave has on that line)
+    struct Span { int beg, end; };
+    auto span_of = [&](int xo) {
+        const long long r0 = wave_row(xo);
+        const int nrows = min(max(twc - wcol, 1), RW);
+        return Span{__builtin_amdgcn_readfirstlane(row_ptr[r0]), __builtin_amdgcn_readfirstlane(row_ptr[r0 + nrows])};
+    };
     // The loads of a pass are issued piece by piece between the rounds of the arithmetic of the
     // pass before (see compute): a wave that issues them in one go sits in the issue of its
     // 2 * NLD + 2 load instructions until the memory pipeline has taken all of them, which is most
     // of the time their bytes need, and computes nothing meanwhile (measured: the time of the
     // loads and the time of the arithmetic added up).
     struct IssueState {
-        __amdgpu_buffer_rsrc_t rc, rv;    // wave-uniform descriptors: the span's first entry to the arrays' end
+        __amdgpu_buffer_rsrc_t rc, rv;    // wave-uniform descriptors of the span, from its first entry (rounded down to 16 bytes) to its end
         long long row;                    // this lane's row (clamped into the segment)
     };
     constexpr int NPIECE = 2 * NLD + 2;
     constexpr int kStreamAux = 2;     // cache policy of the entry loads: non-temporal (every line is used once; measured 3 % faster)
-    auto issue_begin = [&](int xo, int sb, IssueState &st, int &sb4) {
-        sb4 = sb & ~3;                                               // 16-byte aligned in both arrays
-        const long long left = ((long long)g.nnz - sb4) * 4;         // bytes from there to the arrays' end
-        const int bytes = (int)(left > 0xfffffffcLL ? 0xfffffffcLL : left);
+    auto issue_begin = [&](int xo, Span sp, IssueState &st, int &sb4) {
+        sb4 = sp.beg & ~3;                                           // 16-byte aligned in both arrays
+        // the descriptors end where the span ends: lanes past it fetch nothing and read zeros
+        // (the image holds a multiple of 256 entries, up to a seventh more than a span)
+        const int bytes = max(min(sp.end, g.nnz) - sb4, 0) * 4;
         constexpr int kRsrcFlags = 0x00020000;                       // raw buffer of 32-bit elements, gfx9 encoding
         st.rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(col_idx + sb4), 0, bytes, kRsrcFlags);
         st.rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(vals + sb4), 0, bytes, kRsrcFlags);
@@ -175,9 +182,9 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
             pl.end = row_ptr[st.row + 1];
         }
     };
-    auto issue = [&](int xo, int sb, PassLoads &pl, int &sb4) {      // all pieces at once (before the march)
+    auto issue = [&](int xo, Span sp, PassLoads &pl, int &sb4) {     // all pieces at once (before the march)
         IssueState st;
-        issue_begin(xo, sb, st, sb4);
+        issue_begin(xo, sp, st, sb4);
         static_for<NPIECE>([&](auto p_tag) { issue_piece(p_tag, st, pl); });
     };
     // registers -> the wave's LDS image; the row of this lane: position of its first entry in the
@@ -396,7 +403,7 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
     const int npass = (xb - xa + WL - 1) / WL;             // uniform over the workgroup
     PassLoads pl_a, pl_b;
     int sb4_a, sb4_b;
-    issue(xa + wline, span_begin(xa + wline), pl_a, sb4_a);
+    issue(xa + wline, span_of(xa + wline), pl_a, sb4_a);
     {   // lines of the first step -> LDS
         const int lo = line_lo(xa), hi = line_hi(xa, WL);
         const int items = (hi - lo) * iwc * NP;
@@ -410,8 +417,8 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
         if (tid < NP) xs[tid * CS + zslot] = elem_t(0.0f);
     }
     land(xa + wline, pl_a, sb4_a);
-    issue(xa + WL + wline, span_begin(xa + WL + wline), pl_b, sb4_b);
-    int sb_next = span_begin(xa + 2 * WL + wline);         // requested a step ahead of the loads that start there
+    issue(xa + WL + wline, span_of(xa + WL + wline), pl_b, sb4_b);
+    Span sp_next = span_of(xa + 2 * WL + wline);        // requested a step ahead of the loads that start there
     __syncthreads();
 
     // one step: the loads of step pass + 2 go into `nw`, those of step pass + 1 land from `old`
@@ -420,8 +427,8 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
         // the ring lines first: they are needed at the end of this step, the entries a step later
         load_next_lines(xa + (pass + 1) * WL);
         IssueState st;
-        issue_begin(xo + 2 * WL, sb_next, st, sb4_nw);
-        sb_next = span_begin(xo + 3 * WL);
+        issue_begin(xo + 2 * WL, sp_next, st, sb4_nw);
+        sp_next = span_of(xo + 3 * WL);
         set_window(xo);
         __builtin_amdgcn_sched_barrier(0);
         compute(xo, st, nw);
