@@ -53,6 +53,8 @@ struct MarchGeom {
     int accum;            // 1: add to y instead of storing (later channels of a multi-channel sum)
     int col_blocks;       // blocks of batch columns (4*NV each, or 1): batch / (4*NV), or batch
     int max_row;          // most entries a row of the matrix has
+    int channels;         // input channels walked inside one launch (spmm_stage_march_kernel with MC), else 1
+    long long x_plane;    // floats between the x planes of two channels
 };
 
 // NV: float4 column chunks per lane (NV planes in LDS, 4*NV batch columns per

@@ -14,7 +14,7 @@
 //  * loads: the entries of a wave's 64 / G consecutive rows are one contiguous span of col_idx and
 //    of vals.  The wave loads that span with 16 bytes per lane, every instruction one contiguous
 //    kilobyte, every memory line touched exactly once (buffer loads: a wave-uniform descriptor that
-//    ends with the arrays, so a piece past their end reads zero), one whole pass ahead of the
+//    ends with the span, so a lane past its end fetches nothing and reads zero), one whole pass ahead of the
 //    arithmetic, and writes the registers into an LDS image of the span at the end of the pass;
 //  * arithmetic: G lanes share a row, lane l takes entries l, l+G, ... of it from the LDS image
 //    (4-byte LDS reads at compile-time offsets), computes the LDS address of the stored column in
@@ -31,6 +31,14 @@
 // registers during the step and registers -> LDS between the two barriers that end it.  Every
 // load of a step -- entries, row bounds, input lines -- is issued at its start and first used
 // at its end, so nothing waits for memory while there is arithmetic left.
+//
+// Several input channels (MC).  The channels share row_ptr and col_idx and have a vals array and
+// an x plane each; y is their sum.  A step is then one block of WL result lines for ONE channel,
+// the channels of a block in turn: the accumulators stay in registers from the first channel of
+// the block to the last, after which the lanes combine and store as usual -- y is written once,
+// never read, and the sum has a fixed order.  The image keeps the block's columns while the
+// channels pass (only the values are loaded again), and the ring is refilled with the whole
+// window of the next channel's plane instead of the lines a block adds.
 #pragma once
 #include <type_traits>
 
@@ -66,8 +74,8 @@ constexpr int stage_plane(int nv, int nld) {
 // chunks per lane (0: one scalar column).  NL: ring lines (power of two, at least the lines WL
 // output lines can touch).  XLD: registers per thread that carry the next step's input lines.
 // NLD: 16-byte loads per lane, array and pass; NLD * 256 >= (64 / G) * longest row + 3.
-// CS: LDS pixels per plane (> NL * iw_pitch).
-template <int G, int NIT, int NV, int NL, int XLD, int NLD, int CS>
+// CS: LDS pixels per plane (> NL * iw_pitch).  MC: walk g.channels input channels per block of lines.
+template <int G, int NIT, int NV, int NL, int XLD, int NLD, int CS, bool MC = false>
 __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(const int *__restrict__ row_ptr,
                                                                             const int *__restrict__ col_idx,
                                                                             const float *__restrict__ vals,
@@ -91,7 +99,7 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
     typedef int ivec4 __attribute__((ext_vector_type(4)));
     static_assert(G == 2 || G == 4 || G == 8, "lanes per row");
     static_assert((NL & (NL - 1)) == 0, "ring size");
-    static_assert(NIT * G + 3 <= CAP && RW * ((NIT - 1) * G + 1) + 3 <= CAP, "image too small for the rows");
+    static_assert(NIT * G + 7 <= CAP && RW * ((NIT - 1) * G + 1) + 3 <= CAP, "image too small for the rows");
     extern __shared__ float4 smem[];
     elem_t *xs = reinterpret_cast<elem_t *>(smem);   // [NP planes][CS pixels]
 
@@ -109,6 +117,7 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
     const int gl = lane % G, gr = lane / G;
     const int wline = wave / WC;                  // this wave's line within a step
     const int wcol = (wave % WC) * RW;            // first strip column of this wave's rows
+    const int nch = MC ? g.channels : 1;
 
     char *lds_tail = reinterpret_cast<char *>(smem) + (size_t)NP * CS * PIXB;
     int *img_c = reinterpret_cast<int *>(lds_tail + wave * stage_wave_bytes(NLD));   // image of the wave's span of col_idx
@@ -154,20 +163,34 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
     // 2 * NLD + 2 load instructions until the memory pipeline has taken all of them, which is most
     // of the time their bytes need, and computes nothing meanwhile (measured: the time of the
     // loads and the time of the arithmetic added up).
+    struct SetInfo {                      // what land() must know of a pass, kept beside its register set
+        int sb4;                          // first entry of the column image (span begin rounded down to 16 bytes)
+        int dv;                           // image index of an entry in the value image minus that in the column image
+        int ch;                           // channel of the pass
+    };
     struct IssueState {
         __amdgpu_buffer_rsrc_t rc, rv;    // wave-uniform descriptors of the span, from its first entry (rounded down to 16 bytes) to its end
         long long row;                    // this lane's row (clamped into the segment)
     };
     constexpr int NPIECE = 2 * NLD + 2;
     constexpr int kStreamAux = 2;     // cache policy of the entry loads: non-temporal (every line is used once; measured 3 % faster)
-    auto issue_begin = [&](int xo, Span sp, IssueState &st, int &sb4) {
-        sb4 = sp.beg & ~3;                                           // 16-byte aligned in both arrays
+    auto issue_begin = [&](int xo, int ch, Span sp, IssueState &st, SetInfo &si) {
+        const int sb4 = sp.beg & ~3;                                 // 16-byte aligned
         // the descriptors end where the span ends: lanes past it fetch nothing and read zeros
         // (the image holds a multiple of 256 entries, up to a seventh more than a span)
-        const int bytes = max(min(sp.end, g.nnz) - sb4, 0) * 4;
+        const int end = min(sp.end, g.nnz);
+        const int bytes = max(end - sb4, 0) * 4;
+        // the values of channel ch start ch * nnz entries further on; their image is aligned on its own
+        const long long vabs = (MC ? (long long)ch * g.nnz : 0) + sp.beg;
+        const long long vb4 = vabs & ~3LL;
+        const int vbytes = MC ? max((int)(vabs - sp.beg + end - vb4), 0) * 4 : bytes;
+        si.sb4 = sb4;
+        si.dv = MC ? (int)(vabs - vb4) - (sp.beg - sb4) : 0;
+        si.ch = ch;
         constexpr int kRsrcFlags = 0x00020000;                       // raw buffer of 32-bit elements, gfx9 encoding
-        st.rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(col_idx + sb4), 0, bytes, kRsrcFlags);
-        st.rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(vals + sb4), 0, bytes, kRsrcFlags);
+        // (the columns are those of the block: loaded with its first channel only)
+        st.rc = __builtin_amdgcn_make_buffer_rsrc(const_cast<int *>(col_idx + sb4), 0, (MC && ch != 0) ? 0 : bytes, kRsrcFlags);
+        st.rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(vals + vb4), 0, vbytes, kRsrcFlags);
         st.row = wave_row(xo) + min(gr, max(twc - 1 - wcol, 0));
     };
     auto issue_piece = [&](auto p_tag, const IssueState &st, PassLoads &pl) {
@@ -182,28 +205,30 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
             pl.end = row_ptr[st.row + 1];
         }
     };
-    auto issue = [&](int xo, Span sp, PassLoads &pl, int &sb4) {     // all pieces at once (before the march)
+    auto issue = [&](int xo, int ch, Span sp, PassLoads &pl, SetInfo &si) {   // all pieces at once (before the march)
         IssueState st;
-        issue_begin(xo, sp, st, sb4);
+        issue_begin(xo, ch, sp, st, si);
         static_for<NPIECE>([&](auto p_tag) { issue_piece(p_tag, st, pl); });
     };
     // registers -> the wave's LDS image; the row of this lane: position of its first entry in the
     // image (plus the lane's slot) and its length
-    int pos = 0, len = 0;
-    auto land = [&](int xo, const PassLoads &pl, int sb4) {
+    int pos = 0, len = 0, vshift = 0;
+    auto land = [&](int xo, const PassLoads &pl, const SetInfo &si) {
         ivec4 *dc = reinterpret_cast<ivec4 *>(img_c) + lane;
         ivec4 *dv = reinterpret_cast<ivec4 *>(img_v) + lane;
+        if (!MC || si.ch == 0) {
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-            dc[i * kWave] = pl.c[i];
-            dv[i * kWave] = pl.v[i];
+            for (int i = 0; i < NLD; ++i) dc[i * kWave] = pl.c[i];
         }
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) dv[i * kWave] = pl.v[i];
         const bool valid = xo < xb && wcol + gr < twc;
         len = valid ? pl.end - pl.beg : 0;
-        pos = pl.beg - sb4 + gl;
+        pos = pl.beg - si.sb4 + gl;
+        vshift = si.dv;
         // a row the image does not hold (only arrays edited beyond the documented row length
         // can do that) is cut off at the image's end
-        if (pos + (NIT - 1) * G >= CAP) pos = CAP - 1 - (NIT - 1) * G, len = 0;
+        if (pos + min(vshift, 0) < 0 || pos + max(vshift, 0) + (NIT - 1) * G >= CAP) pos = 3, len = 0;
     };
 
     // ---- window state of this wave's line (wave-uniform), in bytes of LDS as in spmm_march_kernel:
@@ -236,10 +261,11 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
 
     // ---- one pass: the lane's NIT slots of its row, then the G partial sums combined and stored.
     // Between the rounds the pieces of the loads two steps ahead are issued into `nw`.
-    auto compute = [&](int xo, const IssueState &st, PassLoads &nw) __attribute__((always_inline)) {
-        float acc[NVAL];
+    float acc[NVAL];                     // (MC: carried from the first channel of a block of lines to the last)
+    const float *xcur = x;               // the plane of the channel being computed
+    auto compute = [&](int xo, const IssueState &st, PassLoads &nw, bool first, bool last) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < NVAL; ++i) acc[i] = 0.0f;
+        for (int i = 0; i < NVAL; ++i) acc[i] = (!MC || first) ? 0.0f : acc[i];
         bool stray = false;              // an in-row entry whose column is not on a resident line
         // A slot is four steps, each fed by the one before: (A) read the stored column and value
         // from the image, (B) turn the column into an LDS address and the value into a weight,
@@ -250,7 +276,7 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
         // out (every register has a compile-time name: slot mod 4, pixel set slot mod 2) and
         // kept in one basic block, in this order, by the scheduling barriers.
         const int *pc = img_c + pos;
-        const float *pv = img_v + pos;
+        const float *pv = img_v + pos + vshift;
         const int rem = len - gl;                    // slot t belongs to the row iff t * G < rem
         int cc[4], addr[4];
         float vv[4], w[4];
@@ -310,20 +336,21 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
 #pragma unroll 1
             for (int t = 0; t < NIT; ++t) {
                 const int c = img_c[pos + t * G];
-                const float v = img_v[pos + t * G];
+                const float v = img_v[pos + vshift + t * G];
                 const bool act = t * G + gl < len;
                 const int dB = (c << SH) - cbaseB;
                 const int di = (int)fmaf((float)dB, inv_nB, half_inv_n);
                 const int djB = dB - __mul24(di, nB);
                 const bool in = (unsigned)(dB - loB) < spanB && (unsigned)djB < iwcB;
                 if (act && !in) {
-                    const elem_t *src = reinterpret_cast<const elem_t *>(x + (long long)c * g.batch + c0);
+                    const elem_t *src = reinterpret_cast<const elem_t *>(xcur + (long long)c * g.batch + c0);
 #pragma unroll
                     for (int q = 0; q < NP; ++q) fma_elem(acc + 4 * q, v, src[q]);
                 }
             }
         }
 
+        if (MC && !last) return;         // (uniform) more channels of this block to come
         // ---- combine the G partial sums of each row; all 64 lanes are active here
         if constexpr (G == 8) {
             combine_step<NVAL, kDppXor7>(acc, (gl & 4) != 0);
@@ -376,8 +403,9 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
     // two barriers that end the step.  Always XLD loads per thread (clamped addresses).
     elem_t xr[XLD];
     int xdst[XLD];                       // LDS pixel index, or -1
-    auto load_next_lines = [&](int xo_next) {
-        const int lo = line_hi(xo_next - WL, WL), hi = line_hi(xo_next, WL);   // new lines [lo, hi)
+    auto load_next_lines = [&](int xo_next, const float *xplane) {
+        // the lines the block at xo_next adds to the one before (MC: its whole window, of another plane)
+        const int lo = MC ? line_lo(xo_next) : line_hi(xo_next - WL, WL), hi = line_hi(xo_next, WL);
         const int items = xo_next < xb ? (hi - lo) * iwc * NP : 0;
 #pragma unroll
         for (int r = 0; r < XLD; ++r) {
@@ -385,7 +413,7 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
             const int q = item / NP, v = item % NP;
             const int dl = div_small(q, inv_iwc), dj = min(q - dl * iwc, max(iwc - 1, 0));
             const int i = min(lo + dl, g.m - 1);
-            const elem_t *src = reinterpret_cast<const elem_t *>(x + ((long long)i * g.n + (j0 + dj)) * g.batch + c0);
+            const elem_t *src = reinterpret_cast<const elem_t *>(xplane + ((long long)i * g.n + (j0 + dj)) * g.batch + c0);
             xr[r] = src[v];
             xdst[r] = item < items ? v * CS + (i & (NL - 1)) * g.iw_pitch + dj : -1;
         }
@@ -396,14 +424,24 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
             if (xdst[r] >= 0) xs[xdst[r]] = xr[r];
     };
 
-    // ---- the march.  Step P is result lines xa + P*WL .. + WL-1; this wave's line is xa + P*WL + wline.
-    // While step P is computed from the LDS image, the loads of step P + 1 are in flight and those
-    // of step P + 2 are issued (two register sets, so the loop is written two steps per round):
-    // memory never waits for the arithmetic or for the exchange at the end of a step.
+    // ---- the march.  Step q is result lines xa + P*WL .. + WL-1 (this wave's: xa + P*WL + wline) of
+    // channel c, with P = q / channels and c = q mod channels (one channel: P = q).
+    // While step q is computed from the LDS image, the loads of step q + 1 are in flight and those
+    // of step q + 2 are issued (two register sets, so the loop is written two steps per round; an
+    // odd count runs one step more, on lines past the segment's end, which holds no row and
+    // stores nothing): memory never waits for the arithmetic or for the exchange at the end of a step.
     const int npass = (xb - xa + WL - 1) / WL;             // uniform over the workgroup
+    const int nsteps = npass * nch;
+    struct At { int blk, ch; };                            // first line of a step's block, its channel
+    auto after = [&](At a) {
+        if (!MC || a.ch + 1 == nch) return At{a.blk + WL, 0};
+        return At{a.blk, a.ch + 1};
+    };
+    auto plane = [&](int ch) { return MC ? x + (long long)ch * g.x_plane : x; };
+    const At at0{xa, 0}, at1 = after(at0), at2 = after(at1);
     PassLoads pl_a, pl_b;
-    int sb4_a, sb4_b;
-    issue(xa + wline, span_of(xa + wline), pl_a, sb4_a);
+    SetInfo si_a, si_b;
+    issue(at0.blk + wline, 0, span_of(at0.blk + wline), pl_a, si_a);
     {   // lines of the first step -> LDS
         const int lo = line_lo(xa), hi = line_hi(xa, WL);
         const int items = (hi - lo) * iwc * NP;
@@ -416,33 +454,37 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
         }
         if (tid < NP) xs[tid * CS + zslot] = elem_t(0.0f);
     }
-    land(xa + wline, pl_a, sb4_a);
-    issue(xa + WL + wline, span_of(xa + WL + wline), pl_b, sb4_b);
-    Span sp_next = span_of(xa + 2 * WL + wline);        // requested a step ahead of the loads that start there
+    land(at0.blk + wline, pl_a, si_a);
+    issue(at1.blk + wline, at1.ch, span_of(at1.blk + wline), pl_b, si_b);
+    Span sp_next = span_of(at2.blk + wline);               // requested a step ahead of the loads that start there
+    At cur = at0, nxt = at1, nxt2 = at2;
     __syncthreads();
 
-    // one step: the loads of step pass + 2 go into `nw`, those of step pass + 1 land from `old`
-    auto step = [&](int pass, PassLoads &nw, int &sb4_nw, const PassLoads &old, int sb4_old) __attribute__((always_inline)) {
-        const int xo = xa + pass * WL + wline;
+    // one step: the loads of step q + 2 go into `nw`, those of step q + 1 land from `old`
+    auto step = [&](PassLoads &nw, SetInfo &si_nw, const PassLoads &old, const SetInfo &si_old) __attribute__((always_inline)) {
+        const int xo = cur.blk + wline;
         // the ring lines first: they are needed at the end of this step, the entries a step later
-        load_next_lines(xa + (pass + 1) * WL);
+        load_next_lines(nxt.blk, plane(nxt.ch));
         IssueState st;
-        issue_begin(xo + 2 * WL, sp_next, st, sb4_nw);
-        sp_next = span_of(xo + 3 * WL);
+        issue_begin(nxt2.blk + wline, nxt2.ch, sp_next, st, si_nw);
+        const At nxt3 = after(nxt2);
+        sp_next = span_of(nxt3.blk + wline);
         set_window(xo);
+        xcur = plane(cur.ch);
         __builtin_amdgcn_sched_barrier(0);
-        compute(xo, st, nw);
+        compute(xo, st, nw, cur.ch == 0, cur.ch == nch - 1);
         __builtin_amdgcn_sched_barrier(0);
         // the wave's own image first (its LDS instructions execute in order, the reads of this
         // step are done), the ring lines once every wave has left the step
-        land(xo + WL, old, sb4_old);
+        land(nxt.blk + wline, old, si_old);
         __syncthreads();
         store_next_lines();
         __syncthreads();
+        cur = nxt, nxt = nxt2, nxt2 = nxt3;
     };
-    for (int pass = 0; pass < npass; pass += 2) {
-        step(pass, pl_a, sb4_a, pl_b, sb4_b);
-        if (pass + 1 < npass) step(pass + 1, pl_b, sb4_b, pl_a, sb4_a);
+    for (int q = 0; q < nsteps; q += 2) {
+        step(pl_a, si_a, pl_b, si_b);
+        if (MC || q + 1 < nsteps) step(pl_b, si_b, pl_a, si_a);
     }
 }
 

@@ -548,6 +548,7 @@ bool march_geometry(const conv_plan *plan, int batch, int nv, int tw, MarchGeom 
 constexpr int kStageNl = 16;
 constexpr int kStageTargetBlocks = 256;
 constexpr int kStageXld = 3;
+constexpr int kStageXldChannels = 5;    // several channels in one launch: every step loads its whole window
 struct StageShape { int g, nit, nld; };
 bool stage_shape(int max_row_nnz, StageShape *out) {
     // Rows of 3 x 3 taps: the fixed cost of a pass is not paid back (224^2, k 3, batch 256: 41 us
@@ -566,7 +567,9 @@ constexpr size_t stage_lds(int nv, int nld) {
            (size_t)kStageWaves * stage_wave_bytes(nld);
 }
 
-bool stage_march_geometry(const conv_plan *plan, int batch, int nv, const StageShape &ss, MarchGeom *out, int *wl_out) {
+// channels > 1: the geometry of one launch that walks the channels of every block of lines
+bool stage_march_geometry(const conv_plan *plan, int batch, int nv, int channels, const StageShape &ss, MarchGeom *out,
+                          int *wl_out) {
     const ConvShape &sh = plan->shape;
     const bool tr = plan->transposed;
     MarchGeom g{};
@@ -579,6 +582,9 @@ bool stage_march_geometry(const conv_plan *plan, int batch, int nv, const StageS
     g.batch = batch;
     g.nnz = (int)plan->nnz;
     g.max_row = plan->max_row_nnz;
+    g.channels = channels;
+    g.x_plane = (long long)plan->cols * batch;
+    if (channels > 1 && (tr || nv == 2)) return false;
     const int tw = kStageTw, rw = kWave / ss.g, wl = kStageWaves / (tw / rw);
     // the image must hold the rows of a wave: (rw - 1) full rows, the slots of the last one, 3 entries of alignment
     if ((int64_t)(rw - 1) * plan->max_row_nnz + (int64_t)ss.nit * ss.g + 3 > (int64_t)ss.nld * 256) return false;
@@ -591,7 +597,10 @@ bool stage_march_geometry(const conv_plan *plan, int batch, int nv, const StageS
     g.iw = (int)iw;
     g.iw_pitch = round_up_mod((int)iw, 16, 8);
     if ((int64_t)kStageNl * g.iw_pitch + 1 > plane) return false;
-    if (fresh * iw * planes > (int64_t)kStageXld * kWave * kStageWaves) return false;     // line registers per thread
+    // line registers per thread
+    if ((channels > 1 ? need * iw * planes > (int64_t)kStageXldChannels * kWave * kStageWaves
+                      : fresh * iw * planes > (int64_t)kStageXld * kWave * kStageWaves))
+        return false;
     // int arithmetic in the kernel, as for the other marching kernel
     if ((int64_t)sh.m + 2LL * sh.p + sh.k >= (1LL << 30) || (int64_t)sh.n + 2LL * sh.p + iw >= (1LL << 30)) return false;
     if ((int64_t)g.m * g.n > (1LL << 27) || 2LL * kStageNl * g.n * 16 > (1LL << 25)) return false;
@@ -637,7 +646,25 @@ ApplyChoice choose_apply(const conv_plan *full, const float *x, const float *y, 
     int ls, nl;
     StageShape ss;
     int wl;
-    if (stage_shape(plan->max_row_nnz, &ss) && stage_march_geometry(plan, batch, c.nv, ss, &mg, &wl)) {
+    if (full->channels > 1 && stage_shape(plan->max_row_nnz, &ss)) {
+        // all channels in one launch (batches of 8, 24, ... columns as float4 chunks of 4)
+        const int nv = c.nv == 2 ? 1 : c.nv;
+        if (stage_march_geometry(plan, batch, nv, full->channels, ss, &mg, &wl)) {
+            c.kind = Kind::StageMarch;
+            c.nv = nv;
+            c.g = ss.g;
+            c.nit = ss.nit;
+            c.tw = kStageTw;
+            c.threads = kStageWaves * kWave;
+            c.lds = stage_lds(c.nv, ss.nld);
+            c.ls = wl;
+            c.nl = kStageNl;
+            c.xld = ss.nld;
+            c.march = mg;
+            return c;
+        }
+    }
+    if (stage_shape(plan->max_row_nnz, &ss) && stage_march_geometry(plan, batch, c.nv, 1, ss, &mg, &wl)) {
         c.kind = Kind::StageMarch;
         c.g = ss.g;
         c.nit = ss.nit;
@@ -811,9 +838,9 @@ bool launch_march(const ApplyChoice &c, const conv_plan *plan, const float *x, f
     }
 }
 
-template <int G, int NIT, int NLD, int NV>
+template <int G, int NIT, int NLD, int NV, bool MC>
 bool launch_stage_march_inst(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
-    auto kern = spmm_stage_march_kernel<G, NIT, NV, kStageNl, kStageXld, NLD, stage_plane(NV, NLD)>;
+    auto kern = spmm_stage_march_kernel<G, NIT, NV, kStageNl, MC ? kStageXldChannels : kStageXld, NLD, stage_plane(NV, NLD), MC>;
     static thread_local bool allowed[64];
     if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
     MarchGeom g = c.march;
@@ -824,21 +851,28 @@ bool launch_stage_march_inst(const ApplyChoice &c, const conv_plan *plan, const 
     return true;
 }
 
-template <int NV>
+template <int NV, bool MC>
 bool launch_stage_march_nv(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
     if (c.g == 2) {
-        if (c.nit == 13) return launch_stage_march_inst<2, 13, 4, NV>(c, plan, x, y, q);
-        return launch_stage_march_inst<2, 25, 7, NV>(c, plan, x, y, q);
+        if (c.nit == 13) return launch_stage_march_inst<2, 13, 4, NV, MC>(c, plan, x, y, q);
+        return launch_stage_march_inst<2, 25, 7, NV, MC>(c, plan, x, y, q);
     }
-    return launch_stage_march_inst<4, 25, 7, NV>(c, plan, x, y, q);
+    return launch_stage_march_inst<4, 25, 7, NV, MC>(c, plan, x, y, q);
 }
 
 bool launch_stage_march(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    if (c.march.channels > 1) {      // plan: all channels (vals of channel ch at vals + ch * nnz)
+        switch (c.nv) {
+            case 0: return launch_stage_march_nv<0, true>(c, plan, x, y, q);
+            case 1: return launch_stage_march_nv<1, true>(c, plan, x, y, q);
+            default: return launch_stage_march_nv<4, true>(c, plan, x, y, q);
+        }
+    }
     switch (c.nv) {
-        case 0: return launch_stage_march_nv<0>(c, plan, x, y, q);
-        case 1: return launch_stage_march_nv<1>(c, plan, x, y, q);
-        case 2: return launch_stage_march_nv<2>(c, plan, x, y, q);
-        default: return launch_stage_march_nv<4>(c, plan, x, y, q);
+        case 0: return launch_stage_march_nv<0, false>(c, plan, x, y, q);
+        case 1: return launch_stage_march_nv<1, false>(c, plan, x, y, q);
+        case 2: return launch_stage_march_nv<2, false>(c, plan, x, y, q);
+        default: return launch_stage_march_nv<4, false>(c, plan, x, y, q);
     }
 }
 
@@ -1129,7 +1163,10 @@ int conv_spmv(const conv_plan *plan, const float *x_dev, float *y_dev, int batch
         return scope.ok() ? CONV_OK : CONV_EHIP;
     }
     const ApplyChoice c = choose_apply(plan, x_dev, y_dev, batch);
-    if (c.kind == Kind::March || c.kind == Kind::Tile || c.kind == Kind::StageMarch) {
+    if (c.kind == Kind::StageMarch && c.march.channels > 1) {
+        // one launch walks the channels of every block of lines: y is stored once, in a fixed order of sums
+        if (!launch_stage_march(c, plan, x_dev, y_dev, q)) return CONV_EHIP;
+    } else if (c.kind == Kind::March || c.kind == Kind::Tile || c.kind == Kind::StageMarch) {
         // one launch per channel: the first stores y, the others add to it
         conv_plan one = *plan;
         one.cols = plan->cols / plan->channels;
@@ -1565,7 +1602,8 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch) {
     }
     if (plan->channels > 1) {
         const size_t len = strlen(name);
-        const bool per_channel = c.kind == Kind::March || c.kind == Kind::Tile || c.kind == Kind::StageMarch;
+        const bool per_channel = c.kind == Kind::March || c.kind == Kind::Tile ||
+                                 (c.kind == Kind::StageMarch && c.march.channels <= 1);
         snprintf(name + len, sizeof name - len, per_channel ? "_x%d_launches" : "_%d_channels", plan->channels);
     }
     return name;

@@ -241,3 +241,94 @@ def test_channels_in_one_launch_follow_edited_descriptors():
     changed = np.where(np.any(np.abs(got - ref) > REL_TOL * scale + 1e-30, axis=1))[0].tolist()
     assert set(changed) == {r_small, r_moved, r_empty}
     plan.close()
+
+
+# ---- CSR storage, marching kernel: the channels of a block of lines walked inside one launch
+
+def _check_march_channels(shape, channels, batch, seed=3, edit=None):
+    m, n, k, s, p = shape
+    x, K = _case(shape, channels, batch, seed)
+    plan = cs.conv_csr_build_channels(m, n, k, s, p, torch.from_numpy(K).to(device()), channels)
+    cs.conv_plan_set_march_min_jobs(plan, 1)       # test hook: small problems take the marching kernel too
+    variant = plan.variant(batch)
+    assert variant.startswith("lds_march_staged") and variant.endswith("_%d_channels" % channels), variant
+    xd = torch.from_numpy(x).to(device())
+    y = torch.full((plan.rows * batch,), float("nan"), dtype=torch.float32, device=device())
+    cs.conv_spmv(plan, xd, y, batch=batch)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    ref, scale = oracle.conv_channels(m, n, k, s, p, x, K, channels, batch=batch, want_scale=True)
+    assert not np.any(np.isnan(got)), shape
+    assert np.all(got[scale == 0] == 0.0), shape
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    assert np.all(err <= REL_TOL * scale), (shape, channels, batch, float(np.max(err / np.maximum(scale, 1e-300))))
+    # the sum has a fixed order: a second launch gives the same bits
+    y2 = torch.full_like(y, float("nan"))
+    cs.conv_spmv(plan, xd, y2, batch=batch)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.view(np.uint32), y2.cpu().numpy().view(np.uint32))
+    return plan, x, K, got
+
+
+@pytest.mark.parametrize("shape,channels,batch", [
+    ((37, 53, 7, 1, 3), 3, 16),        # nnz odd: the value arrays of channels 1, 2 start off a 16-byte boundary
+    ((130, 97, 7, 1, 3), 2, 4),
+    ((200, 150, 7, 1, 3), 3, 16),      # several strips and segments, ragged in both directions
+    ((131, 70, 5, 1, 2), 4, 8),        # batch 8: float4 chunks of 4 columns, two column blocks
+    ((128, 128, 9, 1, 4), 2, 1),       # SpMV, four lanes per row
+    ((90, 120, 7, 1, 0), 5, 32),       # no padding; two column blocks of 16
+    ((65, 33, 4, 1, 2), 7, 12),        # even kernel, strip of one column plus a full one
+    ((40, 300, 6, 1, 5), 2, 16),       # p close to k: short rows at the borders
+])
+def test_march_channel_sum_in_one_launch(shape, channels, batch):
+    plan, _, _, _ = _check_march_channels(shape, channels, batch)
+    plan.close()
+
+
+def test_march_channel_sum_reads_the_stored_arrays():
+    """Values of one channel and shared columns edited in place: the launch follows the arrays
+    (checked against scipy on the edited matrices)."""
+    import scipy.sparse as sp
+    shape, channels, batch = (70, 90, 7, 1, 3), 3, 16
+    m, n, k, s, p = shape
+    plan, x, K, _ = _check_march_channels(shape, channels, batch)
+    rng = np.random.default_rng(5)
+    nnz = plan.nnz
+    vals = plan.vals.cpu().numpy().reshape(channels, nnz).copy()
+    cols = plan.col_idx.cpu().numpy().copy()
+    rp = plan.row_ptr.cpu().numpy()
+    hit = rng.choice(nnz, size=200, replace=False)
+    vals[1, hit] = rng.standard_normal(200).astype(np.float32)
+    far = rng.choice(nnz, size=20, replace=False)          # columns far from the row's window: read from global memory
+    cols[far] = rng.integers(0, m * n, size=20)
+    plan.vals.copy_(torch.from_numpy(vals.reshape(-1)))
+    plan.col_idx.copy_(torch.from_numpy(cols))
+    y = cs.conv_spmv(plan, torch.from_numpy(x).to(device()), batch=batch)
+    torch.cuda.synchronize()
+    X = x.reshape(channels, m * n, batch).astype(np.float64)
+    ref = np.zeros((plan.rows, batch))
+    scale = np.zeros((plan.rows, batch))
+    for ch in range(channels):
+        # (copies: scipy merges duplicate columns of a row in place when asked for abs)
+        T = sp.csr_matrix((vals[ch].astype(np.float64), cols.copy(), rp.copy()), shape=(plan.rows, m * n))
+        ref += T @ X[ch]
+        scale += abs(T) @ np.abs(X[ch])
+    err = np.abs(y.cpu().numpy().reshape(plan.rows, batch).astype(np.float64) - ref)
+    assert np.all(err <= REL_TOL * scale)
+    plan.close()
+
+
+def test_march_channel_sum_headline_shape_sampled():
+    """1024 x 1024, k = 7, three channels, batch 16 (the default dispatch, no test hook): the
+    whole result against the oracle's sum of padded convolutions."""
+    shape, channels, batch = (1024, 1024, 7, 1, 3), 3, 16
+    m, n, k, s, p = shape
+    x, K = _case(shape, channels, batch, 11)
+    plan = cs.conv_csr_build_channels(m, n, k, s, p, torch.from_numpy(K).to(device()), channels)
+    assert plan.variant(batch).startswith("lds_march_staged") and plan.variant(batch).endswith("_3_channels")
+    y = cs.conv_spmv(plan, torch.from_numpy(x).to(device()), batch=batch)
+    torch.cuda.synchronize()
+    ref, scale = oracle.conv_channels(m, n, k, s, p, x, K, channels, batch=batch, want_scale=True)
+    err = np.abs(y.cpu().numpy().astype(np.float64) - ref.astype(np.float64))
+    assert np.all(err <= REL_TOL * scale)
+    plan.close()
