@@ -530,8 +530,15 @@ def main():
         cm, cn, ck, cs_, cp, cc = 56, 56, 3, 1, 1, 64
         Kc = torch.empty(cc * ck * ck, dtype=torch.float32, device=dev).normal_()
         xc = torch.empty(cc * cm * cn * w.batch, dtype=torch.float32, device=dev).normal_()
-        for tag, pl in (("channel_sum_csr", cs.conv_csr_build_channels(cm, cn, ck, cs_, cp, Kc, cc)),
-                        ("channel_sum_compact", cs.conv_compact_build(cm, cn, ck, cs_, cp, Kc, channels=cc))):
+        # ... and a sum over 3 channels at this workload's own shape (CSR: the marching kernel walks the
+        # channels inside one launch when the shape takes it)
+        K3 = torch.empty(3 * k * k, dtype=torch.float32, device=dev).normal_()
+        x3 = torch.empty(3 * m * n * w.batch, dtype=torch.float32, device=dev).normal_()
+        for tag, pl, (cm, cn, ck, cs_, cp, cc), xc in (
+                ("channel_sum_csr", cs.conv_csr_build_channels(cm, cn, ck, cs_, cp, Kc, cc), (cm, cn, ck, cs_, cp, cc), xc),
+                ("channel_sum_compact", cs.conv_compact_build(cm, cn, ck, cs_, cp, Kc, channels=cc), (cm, cn, ck, cs_, cp, cc), xc),
+                ("channel_sum_csr_3_at_shape", cs.conv_csr_build_channels(m, n, k, s, p, K3, 3), (m, n, k, s, p, 3), x3),
+                ("channel_sum_compact_3_at_shape", cs.conv_compact_build(m, n, k, s, p, K3, channels=3), (m, n, k, s, p, 3), x3)):
             yc = torch.empty(pl.rows * w.batch, dtype=torch.float32, device=dev)
             for _ in range(20):
                 cs.conv_spmv(pl, xc, yc, batch=w.batch)

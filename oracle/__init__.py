@@ -40,7 +40,9 @@ def _load():
     global _lib
     with _lock:
         if _lib is None:
-            lib = ctypes.CDLL(build())
+            # CONV_ORACLE_LIB: a library to load instead (tests/test_oracle_planted_mistakes.py compiles
+            # copies of conv_oracle.c with one mistake each and checks that the pins catch it)
+            lib = ctypes.CDLL(os.environ.get("CONV_ORACLE_LIB") or build())
             i, i64, vp = ctypes.c_int, ctypes.c_int64, ctypes.c_void_p
             lib.oracle_out_shape.argtypes = [i] * 5 + [ctypes.POINTER(i64)] * 2
             lib.oracle_out_shape.restype = i
