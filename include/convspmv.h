@@ -244,7 +244,8 @@ typedef struct conv_dispatch {
                                7 scatter with the sums of a tile of pixels kept on chip, 8 direct scatter
                                (storage 3; for 7: strip x segment = pixels x lines of a tile, ring_lines_needed
                                x lines_per_step = runs x rows of its window, lanes_per_row = columns per step),
-                               9 LDS march with one lane per row */
+                               9 LDS march with the entry stream staged through LDS,
+                               10 row groups over the structure-aware storage (small products) */
     int threads;            /* per workgroup */
     int64_t lds_bytes;      /* dynamic LDS per workgroup */
     int64_t workgroups;     /* that do work, over the whole launch (per channel for kernel 3) */

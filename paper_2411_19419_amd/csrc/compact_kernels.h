@@ -89,11 +89,13 @@ constexpr int kCompactThreads = 256;
 // path only, k, s, rv, nl from the geometry).  LPR lanes share a row, each with 4
 // batch columns (SCALAR: one lane, one column).  RV output lines per lane and step,
 // NL ring lines, XLD registers per thread that carry the next step's input lines
-// (0: the lines are copied after the step instead, behind a barrier).  ACC: the rectangle
+// (0: the lines are copied after the step instead, behind a barrier; on the described path,
+// whose ring holds the lines of one step only, the registers are written to LDS between two
+// barriers after the step).  ACC: the rectangle
 // path adds to y (a later channel of a multi-channel sum); a compile-time switch there, so that
 // the single-channel kernel carries none of it; the described path looks at g.accum.
 template <int KK, int SS, int LPR, bool SCALAR, int RV, int NL, int XLD, bool ACC>
-__global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const int2 *__restrict__ desc,
+__global__ __launch_bounds__(kCompactThreads, (KK == 0 && XLD > 0) ? 1 : 2) void spmm_compact_kernel(const int2 *__restrict__ desc,
                                                                           const float *__restrict__ ktab,
                                                                           const float *__restrict__ x,
                                                                           float *__restrict__ y, CompactGeom g) {
@@ -409,13 +411,74 @@ __global__ __launch_bounds__(kCompactThreads, 2) void spmm_compact_kernel(const 
             load_desc(xo + rv, d_nxt);
         }
         compute(xo);
-        if constexpr (XLD > 0) {
+        if constexpr (XLD > 0 && FAST) {
+            store_next();
+            __syncthreads();
+        } else if constexpr (XLD > 0) {
+            __syncthreads();          // the ring holds this step's lines only: everyone has to be done with them
             store_next();
             __syncthreads();
         } else if (ring) {
             __syncthreads();
             if (xo + rv < xb) copy_lines(max(end_line(xo), first_line(xo + rv)), end_line(xo + rv));
             __syncthreads();
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Small products: G lanes per row, x from global memory
+// ---------------------------------------------------------------------------
+// A plane of a few ten thousand outputs gives the marching kernel fewer workgroups than the
+// chip has compute units, and one lane per row leaves most of them idle.  Here G lanes share a
+// row: lane l takes taps l, l + G, ... of the rectangle its descriptor describes (tap t is
+// (da, db) = (t / r2, t mod r2), column base + da*n + db, value ktab[(a_lo + da)*k + b_lo + db]),
+// the partial sums meet in a DPP butterfly, lane 0 of the group stores.  Whatever the descriptor
+// says is what is summed.  blockIdx.y walks the batch columns (4 at a time, or one).
+template <int G, bool SCALAR>
+__global__ __launch_bounds__(kCompactThreads) void spmm_compact_gather_kernel(const int2 *__restrict__ desc,
+                                                                             const float *__restrict__ ktab,
+                                                                             const float *__restrict__ x,
+                                                                             float *__restrict__ y, int rows, int n, int k,
+                                                                             int batch, int accum) {
+    using elem_t = typename std::conditional<SCALAR, float, vec4>::type;
+    constexpr int NCOL = SCALAR ? 1 : 4;
+    const long long row = ((long long)blockIdx.x * kCompactThreads + threadIdx.x) / G;
+    const int lane = (int)threadIdx.x % G;
+    int2 d = make_int2(0, 0);
+    if (row < rows) d = desc[row];
+    const unsigned w = (unsigned)d.y;
+    const int a_lo = w & 255u, r1 = (w >> 8) & 255u, b_lo = (w >> 16) & 255u, r2 = w >> 24;
+    const int cnt = r1 * r2;                               // at most 255 * 255: div_small is exact
+    const float inv_r2 = 1.0f / (float)max(r2, 1);
+    for (int c0 = blockIdx.y * NCOL; c0 < batch; c0 += gridDim.y * NCOL) {      // uniform over the block
+        elem_t acc = elem_t(0.0f);
+        for (int t = lane; t < cnt; t += G) {
+            const int da = div_small(t, inv_r2), db = t - da * r2;
+            const float kv = ktab[(a_lo + da) * k + b_lo + db];
+            const elem_t e = *reinterpret_cast<const elem_t *>(x + ((long long)d.x + (long long)da * n + db) * batch + c0);
+            if constexpr (SCALAR) {
+                acc = fmaf(kv, e, acc);
+            } else {
+                acc.x = fmaf(kv, e.x, acc.x);
+                acc.y = fmaf(kv, e.y, acc.y);
+                acc.z = fmaf(kv, e.z, acc.z);
+                acc.w = fmaf(kv, e.w, acc.w);
+            }
+        }
+        // every lane of the wave is here (rows past the end have no taps)
+        if constexpr (SCALAR) {
+            acc = group_sum<G>(acc);
+        } else {
+            acc.x = group_sum<G>(acc.x);
+            acc.y = group_sum<G>(acc.y);
+            acc.z = group_sum<G>(acc.z);
+            acc.w = group_sum<G>(acc.w);
+        }
+        if (row < rows && lane == 0) {
+            elem_t *dst = reinterpret_cast<elem_t *>(y + row * batch + c0);
+            if (accum) acc += *dst;       // later channel of a multi-channel sum
+            *dst = acc;
         }
     }
 }

@@ -887,6 +887,8 @@ struct CompactChoice {
     size_t lds;
     unsigned col_blocks;
     CompactGeom geom;
+    int xld;              // described path: registers per thread that carry the next step's lines (0: copied after the step)
+    int gather_g;         // > 0: the row-group kernel with this many lanes per row instead (small products)
 };
 
 // rectangle path instantiations: s = 1 and these k, RV = 4 lines per lane, ring of 16
@@ -898,6 +900,8 @@ constexpr int rect_xld(int k, int s, int lpr) {
     return (rect_rv(s) * s * ((kCompactThreads / lpr - 1) * s + k) * lpr + kCompactThreads - 1) / kCompactThreads;
 }
 constexpr int kCompactTargetBlocks = 512;
+constexpr int kDescXld = 18;                    // described path with the next step's lines prefetched into registers
+constexpr int64_t kCompactMinBlocks = 256;      // below this many workgroups the row-group kernel takes the product
 
 bool rect_compiled(int k, int s) {
     return (s == 1 && (k == 1 || k == 3 || k == 5 || k == 7 || k == 9)) || (s == 2 && (k == 2 || k == 3 || k == 5 || k == 7));
@@ -958,6 +962,13 @@ CompactChoice choose_compact(const conv_plan *plan, const float *x, const float 
                     g.nl = nl;
                     c.lds = (size_t)bytes;
                     found = true;
+                    // the lines a step adds, in registers during the step before: when they fit, and when the
+                    // ring is large enough that the workgroup is alone on its CU anyway (the registers cost
+                    // the second workgroup); a line of x shorter than 2^24 bytes as for the rectangle path
+                    const int64_t fresh = std::min<int64_t>((int64_t)rv * sh.s, need);
+                    c.xld = (bytes > 64 * 1024 && fresh * cw * c.lpr <= (int64_t)kDescXld * kCompactThreads &&
+                             (int64_t)sh.n * batch * 4 < (1LL << 24) && (int64_t)batch * 4 * (kCompactThreads + 1) < (1LL << 31))
+                                ? kDescXld : 0;
                 }
             }
         }
@@ -965,7 +976,10 @@ CompactChoice choose_compact(const conv_plan *plan, const float *x, const float 
     g.tw = tw;
     g.iw = (int)iw;
     g.strips = (sh.n_out + tw - 1) / tw;
-    int64_t segs = kCompactTargetBlocks / ((int64_t)g.strips * c.col_blocks);
+    // two workgroups per CU, or one where the ring leaves room for one only (a segment starts by
+    // loading the whole window of its first step: fewer, longer segments then)
+    const int64_t target = c.lds > kLdsPerCu / 2 ? kCompactTargetBlocks / 2 : kCompactTargetBlocks;
+    int64_t segs = target / ((int64_t)g.strips * c.col_blocks);
     if (segs < 1) segs = 1;
     int64_t seg = (sh.m_out + segs - 1) / segs;
     if (seg < 2 * g.rv) seg = 2 * g.rv;
@@ -977,6 +991,15 @@ CompactChoice choose_compact(const conv_plan *plan, const float *x, const float 
     g.blocks_per_xcd = (int)((jobs + kXcds - 1) / kXcds);
     c.geom = g;
     c.ok = true;
+    // Fewer workgroups than compute units: the marching layout cannot fill the chip.  The
+    // row-group kernel gives such a product rows * G lanes instead (x from global memory, which
+    // for a plane this small means from the L2).
+    // (the plan's marching threshold, a test hook, lowers the bound so that small test shapes march too)
+    if (jobs * c.col_blocks < std::min<int64_t>(kCompactMinBlocks, plan->march_min_jobs) &&
+        plan->rows * 16 / kCompactThreads + 1 < kInt32Limit) {
+        c.gather_g = group_width(sh.k * sh.k);
+        if (!c.scalar) { c.lpr = 1; c.col_blocks = (unsigned)(batch / 4); }
+    }
     return c;
 }
 
@@ -1076,12 +1099,12 @@ void launch_compact_channels(const ChannelsChoice &c, const conv_plan *plan, con
     }
 }
 
-template <int KK, int SS, int LPR, bool SCALAR, bool ACC>
+template <int KK, int SS, int LPR, bool SCALAR, bool ACC, int XD = 0>
 bool launch_compact_one(const CompactChoice &c, const CompactGeom &g, const conv_plan *plan, const float *ktab,
                         const float *x, float *y, dim3 grid, hipStream_t q) {
     constexpr bool FAST = KK > 0;
     auto kern = spmm_compact_kernel<KK, SS, LPR, SCALAR, FAST ? rect_rv(SS) : 0, FAST ? kRectNl : 0,
-                                    FAST ? rect_xld(KK, SS, LPR) : 0, ACC>;
+                                    FAST ? rect_xld(KK, SS, LPR) : XD, ACC>;
     static thread_local bool allowed[64];
     if (!allow_large_lds(kern, c.lds, plan->device, allowed)) return false;
     kern<<<grid, kCompactThreads, c.lds, q>>>(plan->desc, ktab, x, y, g);
@@ -1101,6 +1124,8 @@ bool launch_compact_inst(const CompactChoice &c, const conv_plan *plan, const fl
             const dim3 grid((unsigned)(c.geom.blocks_per_xcd * kXcds), std::min(kMaxGridY, c.col_blocks - cb));
             const bool ok = (KK > 0 && ch > 0)
                                 ? launch_compact_one<KK, SS, LPR, SCALAR, (KK > 0)>(c, g, plan, plan->ktab + ch * kk, x + ch * plane, y, grid, q)
+                            : (KK == 0 && c.xld > 0)
+                                ? launch_compact_one<KK, SS, LPR, SCALAR, false, (KK == 0 ? kDescXld : 0)>(c, g, plan, plan->ktab + ch * kk, x + ch * plane, y, grid, q)
                                 : launch_compact_one<KK, SS, LPR, SCALAR, false>(c, g, plan, plan->ktab + ch * kk, x + ch * plane, y, grid, q);
             if (!ok) return false;
         }
@@ -1128,7 +1153,32 @@ bool launch_compact_k(const CompactChoice &c, const conv_plan *plan, const float
     }
 }
 
+template <int G>
+void launch_compact_gather(const CompactChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    const unsigned bx = (unsigned)((plan->rows * G + kCompactThreads - 1) / kCompactThreads);
+    const dim3 grid(bx, (unsigned)std::min<unsigned>(c.col_blocks, 65535u));
+    const size_t plane = (size_t)(plan->cols / plan->channels) * c.geom.batch, kk = (size_t)c.geom.k * c.geom.k;
+    for (int ch = 0; ch < plan->channels; ++ch) {      // one launch per channel: the first stores y, the others add to it
+        if (c.scalar)
+            spmm_compact_gather_kernel<G, true><<<grid, kCompactThreads, 0, q>>>(plan->desc, plan->ktab + ch * kk, x + ch * plane, y,
+                                                                             (int)plan->rows, c.geom.n, c.geom.k, c.geom.batch, ch > 0);
+        else
+            spmm_compact_gather_kernel<G, false><<<grid, kCompactThreads, 0, q>>>(plan->desc, plan->ktab + ch * kk, x + ch * plane, y,
+                                                                              (int)plan->rows, c.geom.n, c.geom.k, c.geom.batch, ch > 0);
+    }
+}
+
 bool launch_compact(const CompactChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
+    if (c.gather_g) {
+        switch (c.gather_g) {
+            case 1: launch_compact_gather<1>(c, plan, x, y, q); break;
+            case 2: launch_compact_gather<2>(c, plan, x, y, q); break;
+            case 4: launch_compact_gather<4>(c, plan, x, y, q); break;
+            case 8: launch_compact_gather<8>(c, plan, x, y, q); break;
+            default: launch_compact_gather<16>(c, plan, x, y, q); break;
+        }
+        return true;
+    }
     if (c.scalar) return launch_compact_k<1, true>(c, plan, x, y, q);
     switch (c.lpr) {
         case 1: return launch_compact_k<1, false>(c, plan, x, y, q);
@@ -1510,8 +1560,15 @@ int conv_test_dispatch_info(int m, int n, int k, int s, int p, int batch, int st
     } else if (plan.compact) {
         const CompactChoice cc = choose_compact(&plan, nullptr, nullptr, batch);
         if (!cc.ok) return CONV_EOVERFLOW;
-        d.kernel = cc.kk ? 5 : 4;
+        d.kernel = cc.gather_g ? 10 : (cc.kk ? 5 : 4);
         d.threads = kCompactThreads;
+        if (cc.gather_g) {
+            d.lanes_per_row = cc.gather_g;
+            d.columns_per_lane = cc.scalar ? 1 : 4;
+            d.workgroups = ((plan.rows * cc.gather_g + kCompactThreads - 1) / kCompactThreads) * std::min<int64_t>(cc.col_blocks, 65535);
+            *out = d;
+            return CONV_OK;
+        }
         d.lds_bytes = (int64_t)cc.lds;
         d.strip = cc.geom.tw;
         d.segment = cc.geom.seg;
@@ -1572,12 +1629,14 @@ const char *conv_spmv_variant(const conv_plan *plan, int batch) {
         char cols[16];
         if (cc.scalar) snprintf(cols, sizeof cols, "scalar");
         else snprintf(cols, sizeof cols, "float4x%d", cc.lpr);
-        if (cc.kk)
+        if (cc.gather_g)
+            snprintf(name, sizeof name, "compact_gather_g%d_%s", cc.gather_g, cc.scalar ? "scalar" : "float4x1");
+        else if (cc.kk)
             snprintf(name, sizeof name, "compact_rect_k%ds%d_%dx%d_ring%d_rv%d_%s", cc.kk, cc.ss, cc.geom.seg,
                      cc.geom.tw, cc.geom.nl, cc.geom.rv, cols);
         else
-            snprintf(name, sizeof name, "compact_described_%dx%d_ring%d_rv%d_%s", cc.geom.seg, cc.geom.tw,
-                     cc.geom.nl, cc.geom.rv, cols);
+            snprintf(name, sizeof name, "compact_described_%dx%d_ring%d_rv%d%s_%s", cc.geom.seg, cc.geom.tw,
+                     cc.geom.nl, cc.geom.rv, cc.xld ? "_prefetch" : "", cols);
         return name;
     }
     const ApplyChoice c = choose_apply(plan, nullptr, nullptr, batch);

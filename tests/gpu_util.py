@@ -107,7 +107,8 @@ def check_apply_t(plan, shape, K, u, batch):
 
 def build_plan_c(shape, K):
     m, n, k, s, p = shape
-    return cs.conv_compact_build(m, n, k, s, p, torch.from_numpy(np.ascontiguousarray(K, dtype=np.float32)).to(device()))
+    return _hooked(cs.conv_compact_build(m, n, k, s, p,
+                                         torch.from_numpy(np.ascontiguousarray(K, dtype=np.float32)).to(device())))
 
 
 def check_compact(plan, shape, K):

@@ -188,7 +188,7 @@ def test_channels_in_one_launch_is_what_runs():
     # 56 tiles: every batch gets the narrowest lanes (most workgroups) and all eight ways
     assert plan.variant(16) == "compact_channels_4x16_float4x1_8_ways_8_channels"
     assert plan.variant(12) == "compact_channels_4x16_float4x1_8_ways_8_channels"
-    assert plan.variant(3).startswith("compact_rect")          # batch not a multiple of 4: one launch per channel
+    assert plan.variant(3).startswith("compact_gather")        # batch not a multiple of 4: one launch per channel (small plane: row groups)
     plan.close()
     for shape, channels, batch, want in [((224, 224, 3, 1, 1), 64, 16, "float4x4_4_ways"), ((224, 224, 3, 1, 1), 6, 8, "float4x2_4_ways"),
                                          ((300, 300, 7, 1, 3), 5, 16, "float4x4_4_ways"), ((448, 448, 7, 2, 3), 4, 8, "float4x2_4_ways")]:
@@ -199,7 +199,7 @@ def test_channels_in_one_launch_is_what_runs():
     assert plan.variant(16) == "compact_channels_4x16_float4x1_4_ways_3_channels"      # the fourth wave idles
     plan.close()
     plan = cs.conv_compact_build(m, n, k, s, p, K[:k * k])
-    assert plan.variant(16).startswith("compact_rect")         # one channel: nothing to sum
+    assert plan.variant(16).startswith("compact_gather")       # one channel: nothing to sum
     plan.close()
     plan = cs.conv_compact_build(1024, 1024, 7, 1, 3, torch.zeros(4 * 49, device=device()), channels=4)
     assert plan.variant(16).startswith("compact_rect")         # long products: a launch per channel is no burden

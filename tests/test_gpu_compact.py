@@ -19,6 +19,18 @@ from gpu_util import REL_TOL, build_plan, build_plan_c, check_apply, check_compa
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=["row_groups_where_small", "marching_everywhere"])
+def compact_dispatch(request):
+    """Every test of this file runs twice: with the default dispatch, which gives small products to
+    the row-group kernel, and with the plan's marching threshold lowered to one job (the test
+    hook), so that the small test shapes also take the marching kernel's rectangle and described
+    paths, which the default keeps for large planes."""
+    import gpu_util
+    gpu_util.MARCH_MIN_JOBS = 1 if request.param == "marching_everywhere" else None
+    yield request.param
+    gpu_util.MARCH_MIN_JOBS = None
+
+
 def _rand(shape, batch, seed):
     m, n, k, s, p = shape
     rng = np.random.default_rng(seed)
@@ -74,7 +86,14 @@ def test_compact_shapes(shape, batch):
     plan.close()
 
 
-def test_rectangle_path_is_dispatched_where_compiled():
+def test_rectangle_path_is_dispatched_where_compiled(compact_dispatch):
+    if compact_dispatch != "marching_everywhere":
+        # these shapes are small: by default they go to the row groups
+        for shape, batch in (((37, 53, 7, 1, 3), 16), ((75, 75, 9, 3, 8), 4), ((512, 512, 9, 3, 8), 1)):
+            plan = build_plan_c(shape, np.ones(shape[2] ** 2, dtype=np.float32))
+            assert plan.variant(batch).startswith("compact_gather"), (shape, plan.variant(batch))
+            plan.close()
+        return
     for shape, batch in RECT + RECT_S2:
         plan = build_plan_c(shape, np.ones(shape[2] ** 2, dtype=np.float32))
         assert plan.variant(batch).startswith("compact_rect_k%ds%d" % (shape[2], shape[3])), plan.variant(batch)

@@ -227,13 +227,17 @@ def test_dispatch_geometry_is_consistent_over_many_shapes():
                     groups = 256 // (d["strip"] * d["lanes_per_row"])
                     assert groups >= 1 and 256 % (d["strip"] * d["lanes_per_row"]) == 0
                     assert d["lines_per_step"] % groups == 0 and d["segment"] % d["lines_per_step"] == 0
+                if d["kernel"] == 10:       # row groups over the descriptors: only where marching leaves CUs idle
+                    assert storage == 2 and d["lanes_per_row"] in (1, 2, 4, 8, 16) and d["lds_bytes"] == 0
+                    mo, no = cs.conv_out_shape(m, n, k, s, p)
+                    assert d["workgroups"] >= (mo * no * d["lanes_per_row"] + 255) // 256
                 if storage == 2:
-                    assert d["kernel"] in (4, 5)
+                    assert d["kernel"] in (4, 5, 10)
                 else:
                     assert d["kernel"] in (0, 1, 2, 3, 9)
                     if batch % 4:
                         assert d["columns_per_lane"] == 1
-    assert seen == {0, 1, 2, 3, 4, 5, 9}
+    assert seen == {0, 1, 2, 3, 4, 5, 9, 10}
 
 
 def test_march_edge_grid_dispatch():
@@ -305,13 +309,16 @@ def test_dispatch_of_channel_sums_from_the_structure_aware_storage():
     assert _dispatch(224, 224, 3, 1, 1, 32, 2, 64)["workgroups"] == 56 * 14 * 2
     assert _dispatch(224, 224, 3, 1, 1, 8, 2, 64)["columns_per_lane"] == 8
     assert _dispatch(224, 224, 3, 1, 1, 20, 2, 64)["columns_per_lane"] == 4
-    assert _dispatch(56, 56, 3, 1, 1, 6, 2, 64)["kernel"] == 5          # batch not a multiple of 4
+    assert _dispatch(56, 56, 3, 1, 1, 6, 2, 64)["kernel"] == 10         # batch not a multiple of 4 (small plane: row groups)
+    assert _dispatch(448, 448, 3, 1, 1, 6, 2, 64)["kernel"] == 5
     assert _dispatch(56, 56, 3, 1, 1, 16, 2, 3)["threads"] == 256       # fewer channels than waves: the fourth idles
-    assert _dispatch(56, 56, 3, 1, 1, 16, 2, 1)["kernel"] == 5          # one channel: nothing to sum
+    assert _dispatch(56, 56, 3, 1, 1, 16, 2, 1)["kernel"] == 10         # one channel: nothing to sum
+    assert _dispatch(448, 448, 3, 1, 1, 16, 2, 1)["kernel"] == 5
     assert _dispatch(1024, 1024, 7, 1, 3, 16, 2, 64)["kernel"] == 5     # long products
     d = _dispatch(150, 150, 13, 1, 6, 16, 2, 8)                          # 16 x 28 patch: 16 columns per lane do not fit
     assert d["kernel"] == 6 and d["columns_per_lane"] == 8 and d["lds_bytes"] <= 64 * 1024
-    assert _dispatch(100, 100, 40, 1, 20, 16, 2, 8)["kernel"] == 4      # 43 x 55 patch: no fit, described rows
+    assert _dispatch(100, 100, 40, 1, 20, 16, 2, 8)["kernel"] == 10     # 43 x 55 patch: no fit; a small plane, so row groups
+    assert _dispatch(1000, 1000, 40, 1, 20, 16, 2, 8)["kernel"] == 4    # ... described rows on a large one
     for k, s in ((1, 1), (3, 1), (3, 2), (5, 1), (7, 2), (9, 3), (11, 1)):
         for batch in (4, 8, 12, 16, 64):
             for channels in (4, 12, 100):
