@@ -239,12 +239,18 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
     const int nB = g.n * PIXB, pitchB = g.iw_pitch * PIXB, zslotB = zslot * PIXB;
     const unsigned iwcB = (unsigned)iwc * PIXB;
     const float inv_nB = g.inv_n / (float)PIXB, half_inv_n = 0.5f * g.inv_n;
-    int cbaseB = 0, loB = 0;
+    int cbaseB = 0, loB = 0, neg_cbaseB = 0;
     unsigned spanB = 0;
+    // (-n * PIXB and -cbaseB as values of their own: added in a shift-add and a multiply-add, where
+    // the compiler otherwise subtracts first and pays an instruction more per slot)
+    int neg_nB = -nB;
+    asm volatile("" : "+s"(neg_nB));
     auto set_window = [&](int xo) {
         const int lo = line_lo(xo), hi = line_hi(xo, 1);
         const int ibase = lo & ~(NL - 1);
         cbaseB = (ibase * g.n + j0) * PIXB;
+        neg_cbaseB = -cbaseB;
+        asm volatile("" : "+s"(neg_cbaseB));
         loB = (lo - ibase) * nB;
         spanB = (unsigned)(hi - lo) * (unsigned)nB;
     };
@@ -288,9 +294,9 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
         auto step_b = [&](int t) {
             const int u = t & 3;
             const bool act = t * G < rem;
-            const int dB = (cc[u] << SH) - cbaseB;
+            const int dB = (cc[u] << SH) + neg_cbaseB;
             const int di = (int)fmaf((float)dB, inv_nB, half_inv_n);
-            const int djB = dB - __mul24(di, nB);
+            const int djB = __mul24(di, neg_nB) + dB;
             const bool in = (unsigned)(dB - loB) < spanB && (unsigned)djB < iwcB;
             stray |= act && !in;
             int a = __mul24(di & (NL - 1), pitchB) + djB;
