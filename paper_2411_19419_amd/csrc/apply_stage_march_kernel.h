@@ -178,12 +178,14 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
         const int sb4 = sp.beg & ~3;                                 // 16-byte aligned
         // the descriptors end where the span ends: lanes past it fetch nothing and read zeros
         // (the image holds a multiple of 256 entries, up to a seventh more than a span)
-        const int end = min(sp.end, g.nnz);
+        // (a line past the segment's end -- the loads run two steps ahead of the arithmetic -- has an
+        // empty span: nothing is fetched for it)
+        const int end = xo < xb ? min(sp.end, g.nnz) : sb4;
         const int bytes = max(end - sb4, 0) * 4;
         // the values of channel ch start ch * nnz entries further on; their image is aligned on its own
         const long long vabs = (MC ? (long long)ch * g.nnz : 0) + sp.beg;
         const long long vb4 = vabs & ~3LL;
-        const int vbytes = MC ? max((int)(vabs - sp.beg + end - vb4), 0) * 4 : bytes;
+        const int vbytes = MC ? (xo < xb ? max((int)(vabs - sp.beg + end - vb4), 0) * 4 : 0) : bytes;
         si.sb4 = sb4;
         si.dv = MC ? (int)(vabs - vb4) - (sp.beg - sb4) : 0;
         si.ch = ch;
