@@ -169,8 +169,11 @@ def _word(a_lo, r1, b_lo, r2):
 
 
 @pytest.mark.parametrize("shape,batch", [((96, 300, 7, 1, 3), 16), ((96, 300, 7, 1, 3), 1), ((120, 200, 5, 2, 2), 8),
-                                         ((60, 70, 40, 1, 20), 4)])
-def test_compact_apply_reads_the_stored_descriptors(shape, batch):
+                                         ((60, 70, 40, 1, 20), 4),
+                                         # strides 3 and 4: row groups by default; with the marching threshold
+                                         # lowered the described path, the second with its lines prefetched
+                                         ((150, 160, 9, 3, 8), 1), ((300, 1200, 11, 4, 5), 4)])
+def test_compact_apply_reads_the_stored_descriptors(shape, batch, compact_dispatch):
     """Descriptors and table edited after the build: the product follows them.  Edits:
     shortened and shifted rectangles in the interior (a wave that holds one leaves the
     rectangle path), an emptied row, a row moved to lines far from its window (taps not
@@ -179,6 +182,11 @@ def test_compact_apply_reads_the_stored_descriptors(shape, batch):
     mo, no = oracle.out_shape(*shape)
     x, K = _rand(shape, batch, 21)
     plan = build_plan_c(shape, K)
+    if shape[3] >= 3:
+        want = "compact_described" if compact_dispatch == "marching_everywhere" else "compact_gather"
+        assert plan.variant(batch).startswith(want), plan.variant(batch)
+        if shape[3] == 4 and compact_dispatch == "marching_everywhere":
+            assert "_prefetch_" in plan.variant(batch), plan.variant(batch)
     desc = plan.row_desc.cpu().numpy().copy()
     ktab = plan.ktab.cpu().numpy().copy()
     rng = np.random.default_rng(8)
