@@ -173,7 +173,17 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
         long long row;                    // this lane's row (clamped into the segment)
     };
     constexpr int NPIECE = 2 * NLD + 2;
-    constexpr int kStreamAux = 2;     // cache policy of the entry loads: non-temporal (every line is used once; measured 3 % faster)
+    // Cache policy of the entry loads.  Every line is used once, so non-temporal loads (which the
+    // L2 drops first) keep x resident; but the memory system moves more when the traffic is a mix
+    // of both kinds: with all entry loads non-temporal the headline product takes 98.8 us, with
+    // none 108 us, with two of the seven kilobytes per array and pass loaded normally 91 us; at
+    // batch 1, where x is 1 % of the bytes, three of seven are best (73.8 -> 66.1 us; four: 70.8,
+    // all: 79 us).  About 35-40 % of all bytes on the normal path, that is: the first NCACHED
+    // pieces of each array.
+    constexpr int kStreamAux = 2;
+    // (several channels: every step reloads its whole window of x with normal loads, and no mix of
+    // the entry loads measured better than all of them non-temporal)
+    constexpr int NCACHED = MC ? 0 : (NLD * (NV == 4 ? 29 : 43) + 50) / 100;
     auto issue_begin = [&](int xo, int ch, Span sp, IssueState &st, SetInfo &si) {
         const int sb4 = sp.beg & ~3;                                 // 16-byte aligned
         // the descriptors end where the span ends: lanes past it fetch nothing and read zeros
@@ -199,8 +209,9 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
         constexpr int P = decltype(p_tag)::value;
         if constexpr (P < 2 * NLD) {
             constexpr int i = P / 2;
-            if constexpr (P % 2 == 0) pl.c[i] = __builtin_amdgcn_raw_buffer_load_b128(st.rc, lane * 16, i * 1024, kStreamAux);
-            else pl.v[i] = __builtin_amdgcn_raw_buffer_load_b128(st.rv, lane * 16, i * 1024, kStreamAux);
+            constexpr int AUX = i < NCACHED ? 0 : kStreamAux;
+            if constexpr (P % 2 == 0) pl.c[i] = __builtin_amdgcn_raw_buffer_load_b128(st.rc, lane * 16, i * 1024, AUX);
+            else pl.v[i] = __builtin_amdgcn_raw_buffer_load_b128(st.rv, lane * 16, i * 1024, AUX);
         } else if constexpr (P == 2 * NLD) {
             pl.beg = row_ptr[st.row];
         } else {
