@@ -78,21 +78,46 @@ def _build(src_text, path):
     return path
 
 
-def _pins_pass(lib):
+# the pin file that covers a function of the oracle comes first in the child's run (it stops at the
+# first failure), the others follow
+FIRST = {"oracle_csc": 1, "oracle_conv_t": 1, "oracle_compact_rows": 2, "oracle_compact_decode": 2,
+         "oracle_conv_channels": 3}
+
+
+def _pins_pass(lib, func=None):
     env = dict(os.environ, CONV_ORACLE_LIB=lib, OMP_NUM_THREADS="2")
-    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", *PIN_FILES],
+    first = FIRST.get(func, 0)
+    files = [PIN_FILES[first]] + [f for i, f in enumerate(PIN_FILES) if i != first]
+    r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider", *files],
                        cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     return r.returncode == 0, r.stdout[-2000:]
 
 
-def test_the_unchanged_copy_passes_every_pin(tmp_path):
-    ok, out = _pins_pass(_build(open(SRC).read(), str(tmp_path / "same.so")))
+@pytest.fixture(scope="module")
+def outcomes(tmp_path_factory):
+    """Every mutant (and the unchanged copy, under the key None) built and run against the pins, a
+    few children at a time: {name: (pins passed, tail of the child's output)}."""
+    from concurrent.futures import ThreadPoolExecutor
+    root = tmp_path_factory.mktemp("mutants")
+    src = open(SRC).read()
+    jobs = [(None, None, src)] + [(name, func, _plant(src, func, old, new)) for name, func, old, new in MISTAKES]
+
+    def run(job):
+        idx, (name, func, text) = job
+        return name, _pins_pass(_build(text, str(root / ("lib%d.so" % idx))), func)
+
+    workers = max(1, min(6, len(os.sched_getaffinity(0))))
+    with ThreadPoolExecutor(max_workers=workers) as pool:
+        return dict(pool.map(run, enumerate(jobs)))
+
+
+def test_the_unchanged_copy_passes_every_pin(outcomes):
+    ok, out = outcomes[None]
     assert ok, out
 
 
-@pytest.mark.parametrize("name,func,old,new", MISTAKES, ids=[m[0] for m in MISTAKES])
-def test_a_planted_mistake_fails_a_pin(tmp_path, name, func, old, new):
-    lib = _build(_plant(open(SRC).read(), func, old, new), str(tmp_path / "mutant.so"))
-    ok, out = _pins_pass(lib)
+@pytest.mark.parametrize("name", [m[0] for m in MISTAKES])
+def test_a_planted_mistake_fails_a_pin(outcomes, name):
+    ok, out = outcomes[name]
     assert not ok, "no pin noticed: " + name
     assert "Error" in out or "assert" in out or "failed" in out, out      # a failing test, not a crash of the run
