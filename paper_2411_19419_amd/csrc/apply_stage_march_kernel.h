@@ -25,7 +25,8 @@
 //
 // Work mapping.  A workgroup of 8 waves owns a strip of 32 output columns and a segment of output
 // lines and walks down it WL lines per step; a wave owns 64 / G neighbouring rows of one line
-// (G = 2: a whole line of the strip, WL = 8; G = 4: half a line, WL = 4; G = 8: a quarter, WL = 2).
+// (G = 2: a whole line of the strip, WL = 8; G = 4: half a line, WL = 4; G = 8: a quarter, WL = 2;
+// G = 16 compiles too but measured slower than G = 8 where both fit).
 // The input lines the step can touch sit in a ring of NL LDS lines (slot = line mod NL), one
 // plane per float4 chunk of batch columns; the lines the next step adds travel global ->
 // registers during the step and registers -> LDS between the two barriers that end it.  Every
@@ -97,7 +98,7 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
     constexpr int CNT = NVAL >> SCAT;             // finished columns per storing lane
     constexpr int DUP = ilog2(G) - SCAT;          // low lane bits that end up with copies
     typedef int ivec4 __attribute__((ext_vector_type(4)));
-    static_assert(G == 2 || G == 4 || G == 8, "lanes per row");
+    static_assert(G == 2 || G == 4 || G == 8 || G == 16, "lanes per row");
     static_assert((NL & (NL - 1)) == 0, "ring size");
     static_assert(NIT * G + 7 <= CAP && RW * ((NIT - 1) * G + 1) + 3 <= CAP, "image too small for the rows");
     extern __shared__ float4 smem[];
@@ -182,8 +183,10 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
     // pieces of each array.
     constexpr int kStreamAux = 2;
     // (several channels: every step reloads its whole window of x with normal loads, and no mix of
-    // the entry loads measured better than all of them non-temporal)
-    constexpr int NCACHED = MC ? 0 : (NLD * (NV == 4 ? 29 : 43) + 50) / 100;
+    // the entry loads measured better than all of them non-temporal.  Eight lanes per row: the
+    // shapes that take them have long rows and, at 4096^2, k 11, s 4, batch 4, x is a fifth of the
+    // bytes: none 205 us, one of four 216, two 217, three 220.)
+    constexpr int NCACHED = (MC || G >= 8) ? 0 : (NLD * (NV == 4 ? 29 : 43) + 50) / 100;
     auto issue_begin = [&](int xo, int ch, Span sp, IssueState &st, SetInfo &si) {
         const int sb4 = sp.beg & ~3;                                 // 16-byte aligned
         // the descriptors end where the span ends: lanes past it fetch nothing and read zeros
@@ -371,7 +374,12 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
 
         if (MC && !last) return;         // (uniform) more channels of this block to come
         // ---- combine the G partial sums of each row; all 64 lanes are active here
-        if constexpr (G == 8) {
+        if constexpr (G == 16) {
+            combine_step<NVAL, kDppXor15>(acc, (gl & 8) != 0);
+            combine_step<imax(NVAL / 2, 1), kDppXor7>(acc, (gl & 4) != 0);
+            combine_step<imax(NVAL / 4, 1), kDppXor2>(acc, (gl & 2) != 0);
+            combine_step<imax(NVAL / 8, 1), kDppXor1>(acc, (gl & 1) != 0);
+        } else if constexpr (G == 8) {
             combine_step<NVAL, kDppXor7>(acc, (gl & 4) != 0);
             combine_step<imax(NVAL / 2, 1), kDppXor2>(acc, (gl & 2) != 0);
             combine_step<imax(NVAL / 4, 1), kDppXor1>(acc, (gl & 1) != 0);

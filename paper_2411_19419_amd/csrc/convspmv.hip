@@ -551,14 +551,16 @@ constexpr int kStageXld = 3;
 constexpr int kStageXldChannels = 5;    // several channels in one launch: every step loads its whole window
 struct StageShape { int g, nit, nld; };
 bool stage_shape(int max_row_nnz, StageShape *out) {
-    // Rows of 3 x 3 taps: the fixed cost of a pass is not paid back (224^2, k 3, batch 256: 41 us
-    // against 37 us from the tile kernel).  Rows of more than 100 entries would need 8 lanes per
-    // row and two result lines per step; the other marching kernel, with 16 lanes per row, measured
-    // faster there (4096^2, k 11, s 4, batch 4: 246 us against 308 us).
+    // Rows of 3 x 3 taps: the fixed cost of a pass is not paid back (224^2, k 3, batch 256: 37 us
+    // with either this or the tile kernel).  Rows of 101 to 128 entries take 8 lanes per row and
+    // two result lines per step (4096^2, k 11, s 4, batch 4: 205 us against 246 us from the other
+    // marching kernel, which keeps the still longer rows it can hold -- none at present, its limit
+    // is 128 too -- and the shapes whose lines per step this one's registers do not hold).
     if (max_row_nnz < 16) return false;
     if (max_row_nnz <= 26) *out = StageShape{2, 13, 4};
     else if (max_row_nnz <= 50) *out = StageShape{2, 25, 7};
     else if (max_row_nnz <= 100) *out = StageShape{4, 25, 7};
+    else if (max_row_nnz <= 128) *out = StageShape{8, 16, 4};
     else return false;
     return true;
 }
@@ -857,6 +859,7 @@ bool launch_stage_march_nv(const ApplyChoice &c, const conv_plan *plan, const fl
         if (c.nit == 13) return launch_stage_march_inst<2, 13, 4, NV, MC>(c, plan, x, y, q);
         return launch_stage_march_inst<2, 25, 7, NV, MC>(c, plan, x, y, q);
     }
+    if (c.g == 8) return launch_stage_march_inst<8, 16, 4, NV, MC>(c, plan, x, y, q);
     return launch_stage_march_inst<4, 25, 7, NV, MC>(c, plan, x, y, q);
 }
 

@@ -213,10 +213,10 @@ def test_dispatch_geometry_is_consistent_over_many_shapes():
                     rows = k * k if storage == 0 else ((k + s - 1) // s) ** 2
                     assert 16 <= rows <= 128 and d["strip"] in (32, 64) and d["segment"] % 2 == 0
                     assert d["lines_per_step"] in (1, 2) and d["threads"] == 512
-                if d["kernel"] == 9:        # entries staged through LDS: rows of 16 to 100 entries, 2 or 4 lanes per row
+                if d["kernel"] == 9:        # entries staged through LDS: rows of 16 to 128 entries, 2, 4 or 8 lanes per row
                     rows = k * k if storage == 0 else ((k + s - 1) // s) ** 2
-                    assert 16 <= rows <= 100 and d["strip"] == 32 and d["lanes_per_row"] in (2, 4)
-                    assert d["lanes_per_row"] == (2 if rows <= 50 else 4)
+                    assert 16 <= rows <= 128 and d["strip"] == 32 and d["lanes_per_row"] in (2, 4, 8)
+                    assert d["lanes_per_row"] == (2 if rows <= 50 else 4 if rows <= 100 else 8)
                     assert d["lines_per_step"] * d["lanes_per_row"] == 16 and d["threads"] == 512
                     assert d["segment"] % d["lines_per_step"] == 0 and d["ring_lines"] == 16
                 if d["kernel"] == 5:        # rectangle path: only the compiled (k, s)
@@ -377,7 +377,7 @@ def test_dispatch_of_the_product_from_csc_over_many_shapes():
 
 def test_dispatch_of_the_named_workloads():
     want = {"small_32_k3": 0, "strided_256_k5_b64": 2, "headline_1024_k7_b1": 9, "headline_1024_k7_b16": 9,
-            "cnn_224_k3_b256": 2, "padheavy_512_k9_s3": 0, "padheavy_4096_k11_s4_b4": 3}
+            "cnn_224_k3_b256": 2, "padheavy_512_k9_s3": 0, "padheavy_4096_k11_s4_b4": 9}
     for name, kernel in want.items():
         w = workloads.WORKLOADS[name]
         assert _dispatch(*w.shape, w.batch)["kernel"] == kernel, name
