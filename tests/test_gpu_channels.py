@@ -279,6 +279,8 @@ def _check_march_channels(shape, channels, batch, seed=3, edit=None):
     ((90, 120, 7, 1, 0), 5, 32),       # no padding; two column blocks of 16
     ((65, 33, 4, 1, 2), 7, 12),        # even kernel, strip of one column plus a full one
     ((40, 300, 6, 1, 5), 2, 16),       # p close to k: short rows at the borders
+    ((90, 100, 11, 1, 5), 3, 4),       # eight lanes per row
+    ((300, 200, 11, 4, 5), 2, 4),      # ... at stride 4
 ])
 def test_march_channel_sum_in_one_launch(shape, channels, batch):
     plan, _, _, _ = _check_march_channels(shape, channels, batch)

@@ -267,14 +267,14 @@ def test_march_densenet_layer_shapes(march_everywhere, shape, batch):
 
 
 @pytest.mark.parametrize("batch", [1, 16])
-def test_march_reads_the_stored_arrays(march_everywhere, batch):
+@pytest.mark.parametrize("shape", [(96, 80, 7, 1, 3), (96, 80, 9, 1, 4), (96, 80, 11, 1, 5)])   # 2, 4, 8 lanes per row
+def test_march_reads_the_stored_arrays(march_everywhere, shape, batch):
     """Edited arrays under the marching kernel: a column far outside the resident
     lines must be fetched from global memory (the cold path), scaled values scale y."""
-    shape = (96, 80, 7, 1, 3)
     m, n, k, s, p = shape
     x, K = _rand(shape, batch, 23)
     plan = build_plan(shape, K)
-    assert plan.variant(batch).startswith("lds_march")
+    assert plan.variant(batch).startswith("lds_march_staged") and "_g%d_" % {7: 2, 9: 4, 11: 8}[k] in plan.variant(batch)
     xd = torch.from_numpy(x).to(device())
     y0 = cs.conv_spmv(plan, xd, batch=batch).clone()
     plan.vals.mul_(2.0)
