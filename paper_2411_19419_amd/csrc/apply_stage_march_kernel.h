@@ -186,7 +186,8 @@ __global__ __launch_bounds__(kWave *kStageWaves) void spmm_stage_march_kernel(co
     // the entry loads measured better than all of them non-temporal.  Eight lanes per row: the
     // shapes that take them have long rows and, at 4096^2, k 11, s 4, batch 4, x is a fifth of the
     // bytes: none 205 us, one of four 216, two 217, three 220.)
-    constexpr int NCACHED = (MC || G >= 8) ? 0 : (NLD * (NV == 4 ? 29 : 43) + 50) / 100;
+    // Four lanes per row (1024^2, k 9, batch 16): none 162 us, one of seven 156, two 168, three 171.
+    constexpr int NCACHED = (MC || G >= 8) ? 0 : G == 4 ? 1 : (NLD * (NV == 4 ? 29 : 43) + 50) / 100;
     auto issue_begin = [&](int xo, int ch, Span sp, IssueState &st, SetInfo &si) {
         const int sb4 = sp.beg & ~3;                                 // 16-byte aligned
         // the descriptors end where the span ends: lanes past it fetch nothing and read zeros
