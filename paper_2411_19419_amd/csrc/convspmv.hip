@@ -610,10 +610,19 @@ bool stage_march_geometry(const conv_plan *plan, int batch, int nv, int channels
     g.strips = (g.n_out + tw - 1) / tw;
     const int col_blocks = nv ? batch / (4 * nv) : batch;
     if ((int64_t)((g.n_out + 63) / 64) * ((g.m_out + 7) / 8) * col_blocks < plan->march_min_jobs) return false;   // jobs of 64 columns x 8 lines, as for the other kernel
-    int64_t segs = kStageTargetBlocks / ((int64_t)g.strips * col_blocks);
-    if (segs < 1) segs = 1;
-    int64_t seg = (g.m_out + segs - 1) / segs;
-    seg = (seg + wl - 1) / wl * wl;
+    // Segment length.  A workgroup fills a CU, so the launch runs in rounds of 256 workgroups, and a
+    // segment costs its lines plus about two steps for the window and entries it loads before its
+    // first step: the number of segments per strip that minimises rounds x (lines + 2 steps).  (Three
+    // column blocks of 32 strips: 8 segments = 768 workgroups = 3 full rounds, not 2 segments = 192.)
+    int64_t seg = 0, best_cost = -1;
+    for (int64_t segs = 1; segs <= 512 && (segs - 1) * wl < g.m_out; ++segs) {
+        int64_t len = (g.m_out + segs - 1) / segs;
+        len = (len + wl - 1) / wl * wl;
+        const int64_t real = (g.m_out + len - 1) / len;
+        const int64_t rounds = ((int64_t)g.strips * col_blocks * real + kStageTargetBlocks - 1) / kStageTargetBlocks;
+        const int64_t cost = rounds * (len + 2 * wl);
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; seg = len; }
+    }
     g.seg = (int)seg;
     g.segs = (int)((g.m_out + seg - 1) / seg);
     const int64_t jobs = (int64_t)g.strips * g.segs;
