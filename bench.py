@@ -258,7 +258,8 @@ LLC_BYTES = 256 * 1024 * 1024     # Infinity Cache: a working set below this doe
 
 def config_entry(cs, oracle, workloads, name, dev, stream, launches=60):
     """One named workload, single stream: variant, median / min us of event-bracketed launches after
-    the device has settled, model bytes and rate, useful MAC/s, error against the oracle."""
+    the device has settled and the average of the same number of launches back to back, model bytes
+    and rate, useful MAC/s, error against the oracle."""
     import numpy as np
     import torch
     w = workloads.WORKLOADS[name]
@@ -271,6 +272,14 @@ def config_entry(cs, oracle, workloads, name, dev, stream, launches=60):
     pre, _ = precondition(fn, stream, cap_s=0.25)
     ms = event_times_ms(fn, launches, stream)
     med, mn = ms[len(ms) // 2], ms[0]
+    # the same launches back to back between two events (no gap between a launch and its events)
+    r0, r1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    r0.record(stream)
+    for _ in range(launches):
+        fn()
+    r1.record(stream)
+    torch.cuda.synchronize()
+    b2b = r0.elapsed_time(r1) / launches
     ref, scale = oracle.conv(m, n, k, s, p, x_h, K_h, batch=w.batch, want_scale=True)
     got = y.cpu().numpy().astype(np.float64)
     err = np.abs(got - ref.astype(np.float64))
@@ -279,7 +288,9 @@ def config_entry(cs, oracle, workloads, name, dev, stream, launches=60):
     model = plan.model_bytes(w.batch)
     out = {
         "shape": [m, n, k, s, p], "batch": w.batch, "variant": plan.variant(w.batch),
-        "us_median": med * 1e3, "us_min": mn * 1e3, "launches": launches, "precondition_launches": pre,
+        "us_median": med * 1e3, "us_min": mn * 1e3, "us_back_to_back": b2b * 1e3,
+        "frac_of_hbm_peak_back_to_back": model / (b2b * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "launches": launches, "precondition_launches": pre,
         "model_bytes": model, "model_gbs": model / (med * 1e-3) / 1e9,
         "frac_of_hbm_peak": model / (med * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "cache_resident": bool(model < LLC_BYTES),
