@@ -132,7 +132,7 @@ __global__ __launch_bounds__(TW * 8) void spmm_tile_kernel(const int *__restrict
     constexpr int SCAT = ilog2(G) < ilog2(NVAL) ? ilog2(G) : ilog2(NVAL);
     constexpr int CNT = NVAL >> SCAT;             // finished columns per storing lane
     constexpr int DUP = ilog2(G) - SCAT;          // low lane bits that end up with copies
-    static_assert(G == 4 || G == 8 || G == 16, "group width");
+    static_assert(G == 2 || G == 4 || G == 8 || G == 16, "group width");
     static_assert(TW % RW == 0, "a wave pass must not straddle two output lines");
     extern __shared__ float4 smem[];
     float4 *xs = smem;
@@ -297,9 +297,11 @@ __global__ __launch_bounds__(TW * 8) void spmm_tile_kernel(const int *__restrict
             combine_step<NVAL, kDppXor7>(acc, (gl & 4) != 0);
             combine_step<imax(NVAL / 2, 1), kDppXor2>(acc, (gl & 2) != 0);
             combine_step<imax(NVAL / 4, 1), kDppXor1>(acc, (gl & 1) != 0);
-        } else {
+        } else if constexpr (G == 4) {
             combine_step<NVAL, kDppXor2>(acc, (gl & 2) != 0);
             combine_step<imax(NVAL / 2, 1), kDppXor1>(acc, (gl & 1) != 0);
+        } else {
+            combine_step<NVAL, kDppXor1>(acc, (gl & 1) != 0);
         }
 
         // lanes whose DUP low bits are clear hold CNT finished columns of their row,
@@ -311,27 +313,29 @@ __global__ __launch_bounds__(TW * 8) void spmm_tile_kernel(const int *__restrict
         }
     };
 
-    // ---- this wave takes pass wave of every tile line (the block has GPL
-    // waves).  Two register sets alternate so that the loads of the next pass
-    // are in flight during the arithmetic of this one; the steady-state loop
-    // fetches unconditionally.
-    if (wave >= GPL) return;             // launched with more waves than passes per line
-    const int nline = g.th;
+    // ---- the passes of the tile (GPL per output line, line after line) are dealt to the waves
+    // of the block in turn: wave w takes passes w, w + W, w + 2 W, ...  Two register sets
+    // alternate so that the loads of the next pass are in flight during the arithmetic of this
+    // one; the steady-state loop fetches unconditionally (fetch clamps what lies past the tile).
+    const int nwaves = nthreads / kWave;
+    const int total = g.th * GPL;
+    if (wave >= total) return;
+    const int mine = (total - wave + nwaves - 1) / nwaves;       // passes of this wave
     Pass pa, pb;
     fetch(wave, pa);
     int i = 0;
-    for (; i + 2 < nline; i += 2) {
-        fetch(wave + (i + 1) * GPL, pb);
-        compute(wave + i * GPL, pa);
-        fetch(wave + (i + 2) * GPL, pa);
-        compute(wave + (i + 1) * GPL, pb);
+    for (; i + 2 < mine; i += 2) {
+        fetch(wave + (i + 1) * nwaves, pb);
+        compute(wave + i * nwaves, pa);
+        fetch(wave + (i + 2) * nwaves, pa);
+        compute(wave + (i + 1) * nwaves, pb);
     }
-    if (nline - i == 2) {
-        fetch(wave + (i + 1) * GPL, pb);
-        compute(wave + i * GPL, pa);
-        compute(wave + (i + 1) * GPL, pb);
+    if (mine - i == 2) {
+        fetch(wave + (i + 1) * nwaves, pb);
+        compute(wave + i * nwaves, pa);
+        compute(wave + (i + 1) * nwaves, pb);
     } else {
-        compute(wave + i * GPL, pa);
+        compute(wave + i * nwaves, pa);
     }
 }
 

@@ -414,6 +414,7 @@ int group_width(int max_row_nnz) {
 
 constexpr size_t kLdsPerCu = 160 * 1024;
 constexpr int kTileG = 8;
+constexpr int kTileShortRow = 10, kTileShortNit = 5;      // rows this short: 2 lanes per row, 5 slots per lane
 const int kTileNit[] = {2, 4, 7};       // trip counts the tile kernel is built for (8 lanes per row)
 
 // Tile kernel instantiations: output pixels per tile line (threads = 8 * TW)
@@ -708,10 +709,17 @@ ApplyChoice choose_apply(const conv_plan *full, const float *x, const float *y, 
 
     // one LDS tile per workgroup when the rows fit its unrolled trip count and the
     // input window of at least one output line fits the LDS planes
-    const int need = (plan->max_row_nnz + kTileG - 1) / kTileG;
-    int nit = 0;
-    for (int cand : kTileNit)
-        if (cand >= need) { nit = cand; break; }
+    // Rows of at most 10 entries (k = 3): two lanes per row and 5 slots each.  With 8 lanes per
+    // row the kernel is bound by its instructions there (224^2, k 3, batch 256: 18.5 M vector
+    // instructions for 1.8 M multiply-adds, VALU 0.70 busy): 16 slots for 9 entries and a
+    // three-level combine per row.
+    const bool narrow = plan->max_row_nnz <= kTileShortRow;
+    const int tile_g = narrow ? 2 : kTileG;
+    const int need = (plan->max_row_nnz + tile_g - 1) / tile_g;
+    int nit = narrow ? kTileShortNit : 0;
+    if (!narrow)
+        for (int cand : kTileNit)
+            if (cand >= need) { nit = cand; break; }
     if (nit == 0) return c;
     const int tws[2] = {kTileWide, kTileNarrow}, planes[2] = {kPlaneWide, kPlaneNarrow};
     for (int i = 0; i < 2; ++i) {
@@ -719,7 +727,7 @@ ApplyChoice choose_apply(const conv_plan *full, const float *x, const float *y, 
         if (plan->shape.n_out <= kTileNarrow && tws[i] == kTileWide) continue;
         if (!tile_geometry(plan, batch, tws[i], planes[i], &g)) continue;
         c.kind = Kind::Tile;
-        c.g = kTileG;
+        c.g = tile_g;
         c.nit = nit;
         c.tw = tws[i];
         c.threads = tws[i] * 8;
@@ -758,7 +766,7 @@ void launch_gather(const ApplyChoice &c, const conv_plan *plan, const float *x, 
 
 template <int NIT, int NV, int TW, int CS>
 bool launch_tile_inst(const ApplyChoice &c, const conv_plan *plan, const float *x, float *y, hipStream_t q) {
-    auto kern = spmm_tile_kernel<kTileG, NIT, NV, TW, CS>;
+    auto kern = spmm_tile_kernel<(NIT == kTileShortNit ? 2 : kTileG), NIT, NV, TW, CS>;
     // more than 64 KiB of dynamic LDS has to be allowed once per kernel and device
     static thread_local bool allowed[64];
     const int dev = plan->device;
@@ -784,6 +792,7 @@ bool launch_tile_nv(const ApplyChoice &c, const conv_plan *plan, const float *x,
     switch (c.nit) {
         case 2: return launch_tile_tw<2, NV>(c, plan, x, y, q);
         case 4: return launch_tile_tw<4, NV>(c, plan, x, y, q);
+        case kTileShortNit: return launch_tile_tw<kTileShortNit, NV>(c, plan, x, y, q);
         default: return launch_tile_tw<7, NV>(c, plan, x, y, q);
     }
 }
